@@ -1,0 +1,152 @@
+"""fp64 CPU checker for paged decode attention and KV page copies.
+
+TEST INFRASTRUCTURE ONLY.  Imported by ``tests/``, by the smoke check and by the
+benchmark's ``cpu_baseline`` leg; the product package never imports it and it
+never imports the product's binding.  The arithmetic lives in
+``pkv_oracle.c`` (plain C, fp64, the textbook definition restated in that
+file's header); this module compiles it with gcc and marshals numpy arrays.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+import subprocess
+import time
+from typing import Optional
+
+import numpy as np
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_SRC = os.path.join(_HERE, "pkv_oracle.c")
+_SO = os.path.join(_HERE, "libpkv_oracle.so")
+_lib: Optional[ctypes.CDLL] = None
+
+
+def build(force: bool = False) -> str:
+    """Compile the checker with gcc (OpenMP) if missing or stale."""
+    stale = (not os.path.exists(_SO)) or os.path.getmtime(_SO) < os.path.getmtime(_SRC)
+    if force or stale:
+        tmp = _SO + f".tmp{os.getpid()}"
+        subprocess.check_call(["gcc", "-O2", "-fopenmp", "-fPIC", "-shared", "-std=c11",
+                               "-Wall", "-Wextra", "-o", tmp, _SRC, "-lm"])
+        os.replace(tmp, _SO)
+    return _SO
+
+
+def _load() -> ctypes.CDLL:
+    global _lib
+    if _lib is None:
+        lib = ctypes.CDLL(build())
+        i64, p = ctypes.c_int64, ctypes.c_void_p
+        lib.pkv_oracle_paged_decode_attn.argtypes = [p, p, p, p, p, ctypes.c_float, p,
+                                                     i64, i64, i64, i64, i64, i64, i64,
+                                                     ctypes.c_int]
+        lib.pkv_oracle_paged_decode_attn.restype = ctypes.c_int
+        lib.pkv_oracle_kv_blocks_gather.argtypes = [p, p, p, i64, i64, i64]
+        lib.pkv_oracle_kv_blocks_gather.restype = ctypes.c_int
+        lib.pkv_oracle_kv_blocks_scatter.argtypes = [p, p, p, i64, i64, i64]
+        lib.pkv_oracle_kv_blocks_scatter.restype = ctypes.c_int
+        lib.pkv_oracle_max_threads.restype = ctypes.c_int
+        _lib = lib
+    return _lib
+
+
+def max_threads() -> int:
+    return int(_load().pkv_oracle_max_threads())
+
+
+def _c(a: np.ndarray, dtype) -> np.ndarray:
+    a = np.ascontiguousarray(a)
+    if a.dtype != np.dtype(dtype):
+        raise TypeError(f"expected {np.dtype(dtype)}, got {a.dtype}")
+    return a
+
+
+def paged_decode_attn(q, k_pool, v_pool, block_tables, context_lens, scale,
+                      threads: int = 0) -> np.ndarray:
+    """fp64 reference [S, Hq, D] from bf16 bit patterns (uint16 arrays).
+
+    q [S,Hq,D]; k_pool, v_pool [NB,Hkv,B,D]; block_tables int32 [S,MAXB];
+    context_lens int32 [S]; scale is cast to fp32 first, as the library's is.
+    """
+    q = _c(q, np.uint16)
+    k_pool = _c(k_pool, np.uint16)
+    v_pool = _c(v_pool, np.uint16)
+    block_tables = _c(block_tables, np.int32)
+    context_lens = _c(context_lens, np.int32)
+    S, Hq, D = q.shape
+    NB, Hkv, B, D2 = k_pool.shape
+    if v_pool.shape != k_pool.shape or D2 != D or block_tables.shape[0] != S \
+            or context_lens.shape != (S,):
+        raise ValueError("inconsistent shapes")
+    ref = np.empty((S, Hq, D), dtype=np.float64)
+    rc = _load().pkv_oracle_paged_decode_attn(
+        q.ctypes.data, k_pool.ctypes.data, v_pool.ctypes.data, block_tables.ctypes.data,
+        context_lens.ctypes.data, ctypes.c_float(np.float32(scale)), ref.ctypes.data,
+        S, Hq, Hkv, D, B, block_tables.shape[1], NB, int(threads))
+    if rc != 0:
+        raise ValueError(f"oracle rejected its input (code {rc})")
+    return ref
+
+
+def kv_blocks_gather(pool: np.ndarray, block_ids) -> np.ndarray:
+    """Contiguous image [n, ...block shape] of the listed pages of ``pool``."""
+    pool = np.ascontiguousarray(pool)
+    ids = _c(np.asarray(block_ids), np.int32)
+    NB = pool.shape[0]
+    bb = pool.nbytes // NB if NB else 0
+    staging = np.empty((len(ids),) + pool.shape[1:], dtype=pool.dtype)
+    if len(ids) == 0:
+        return staging
+    rc = _load().pkv_oracle_kv_blocks_gather(pool.ctypes.data, ids.ctypes.data,
+                                             staging.ctypes.data, len(ids), bb, NB)
+    if rc != 0:
+        raise ValueError(f"oracle rejected its input (code {rc})")
+    return staging
+
+
+def kv_blocks_scatter(staging: np.ndarray, pool: np.ndarray, block_ids) -> np.ndarray:
+    """A copy of ``pool`` with page ids[i] replaced by staging[i]."""
+    staging = np.ascontiguousarray(staging)
+    out = np.array(pool, copy=True, order="C")
+    ids = _c(np.asarray(block_ids), np.int32)
+    NB = out.shape[0]
+    if len(ids) == 0:
+        return out
+    bb = out.nbytes // NB
+    if staging.nbytes != bb * len(ids):
+        raise ValueError("staging size does not match the id list")
+    rc = _load().pkv_oracle_kv_blocks_scatter(staging.ctypes.data, out.ctypes.data,
+                                              ids.ctypes.data, len(ids), bb, NB)
+    if rc != 0:
+        raise ValueError(f"oracle rejected its input (code {rc})")
+    return out
+
+
+def timed_attn(q, k_pool, v_pool, block_tables, context_lens, scale, threads: int = 0):
+    """(reference, seconds, threads used) for the benchmark's baseline leg."""
+    t0 = time.perf_counter()
+    ref = paged_decode_attn(q, k_pool, v_pool, block_tables, context_lens, scale, threads)
+    dt = time.perf_counter() - t0
+    return ref, dt, (threads if threads > 0 else max_threads())
+
+
+def compare(gpu_bf16_bits: np.ndarray, ref: np.ndarray) -> dict:
+    """max-abs, relative L2 over the whole tensor, worst per-sequence rel-L2."""
+    got = (np.ascontiguousarray(gpu_bf16_bits, dtype=np.uint16).astype(np.uint32)
+           << np.uint32(16)).view(np.float32).astype(np.float64).reshape(ref.shape)
+    diff = got - ref
+    den = float(np.sqrt((ref * ref).sum()))
+    out = {
+        "max_abs": float(np.abs(diff).max()) if diff.size else 0.0,
+        "rel_l2": float(np.sqrt((diff * diff).sum()) / den) if den > 0 else
+        float(np.sqrt((diff * diff).sum())),
+        "worst_seq_rel_l2": 0.0,
+    }
+    if ref.ndim == 3 and ref.shape[0]:
+        num = np.sqrt((diff * diff).reshape(ref.shape[0], -1).sum(1))
+        dn = np.sqrt((ref * ref).reshape(ref.shape[0], -1).sum(1))
+        ok = dn > 0
+        if ok.any():
+            out["worst_seq_rel_l2"] = float((num[ok] / dn[ok]).max())
+    return out

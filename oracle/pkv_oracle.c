@@ -1,0 +1,145 @@
+/*
+ * CPU checker for the paged-decode hot path.  TEST INFRASTRUCTURE ONLY: it is
+ * called by the tests, by the smoke check and by the benchmark's cpu_baseline
+ * leg, never by the product path, and it shares no code with the HIP library.
+ *
+ * What it computes is the plain definition, in fp64, with no blocking, no
+ * running maximum and no partitioning:
+ *
+ *   The decode stage reuses each request's whole KV cache for every generated
+ *   token (paper Section II-A), and the serving engine keeps that cache per
+ *   request in fixed-size pages (Section II-B; the paged serving engine named
+ *   in Section VI).  For request s, query head h, with kvh = h div G
+ *   (G = Hq / Hkv consecutive query heads share one KV head):
+ *
+ *     x_t  = scale * sum_d q[s,h,d] * K[tbl[s][t div B], kvh, t mod B, d]
+ *     m    = max_t x_t ;  w_t = exp(x_t - m) ;  Z = sum_t w_t
+ *     ref[s,h,e] = sum_t (w_t / Z) * V[tbl[s][t div B], kvh, t mod B, e]
+ *
+ *   over t = 0 .. L_s - 1 (L_s counts the token being decoded: its K,V row is
+ *   already in the pool).  L_s = 0 gives a zero row.  Table entries at or
+ *   beyond ceil(L_s/B) and slots at or beyond L_s in the last block are never
+ *   read.  Inputs are bf16 bit patterns widened exactly; scale is the fp32
+ *   value the library is given, widened.
+ *
+ *   Eviction to and reload from the backing store (Section II-B) and
+ *   migration of a request's whole KV cache at the phase boundary
+ *   (Section IV-B, "KV cache transfer overhead") move whole pages:
+ *     gather : staging[i] = pool[ids[i]]     scatter : pool[ids[i]] = staging[i]
+ *   bytewise, everything else untouched.
+ *
+ * Pool layout: [NB, Hkv, B, D] row-major for K and for V.
+ *
+ * Parity pins (tests, CPU only): dense brute force written in numpy on tiny
+ * inputs, a library fp64 attention on de-paged tensors, closed forms (L = 1,
+ * scale = 0, V == 1, a two-token ln 2 case), shift, paging and GQA
+ * invariances; the copies are pinned by numpy fancy indexing.
+ */
+#include <math.h>
+#include <stdint.h>
+#include <stdlib.h>
+#include <string.h>
+#ifdef _OPENMP
+#include <omp.h>
+#endif
+
+static double widen_bf16(uint16_t bits) {
+  uint32_t u = ((uint32_t)bits) << 16;
+  float f;
+  memcpy(&f, &u, sizeof f);
+  return (double)f;
+}
+
+int pkv_oracle_max_threads(void) {
+#ifdef _OPENMP
+  return omp_get_max_threads();
+#else
+  return 1;
+#endif
+}
+
+/* Returns 0, or -1 on a bad argument, -2 if a dereferenced table entry is
+ * outside [0, NB), -3 on allocation failure.  threads <= 0 means "all". */
+int pkv_oracle_paged_decode_attn(const uint16_t* q, const uint16_t* k_pool,
+                                 const uint16_t* v_pool, const int32_t* block_tables,
+                                 const int32_t* context_lens, float scale, double* ref,
+                                 int64_t S, int64_t Hq, int64_t Hkv, int64_t D, int64_t B,
+                                 int64_t MAXB, int64_t NB, int threads) {
+  if (S < 0 || Hq <= 0 || Hkv <= 0 || D <= 0 || B <= 0 || MAXB <= 0 || Hq % Hkv) return -1;
+  const int64_t G = Hq / Hkv;
+  for (int64_t s = 0; s < S; ++s) {
+    int64_t L = context_lens[s];
+    if (L < 0 || (L + B - 1) / B > MAXB) return -1;
+    for (int64_t j = 0; j < (L + B - 1) / B; ++j) {
+      int64_t pb = block_tables[s * MAXB + j];
+      if (pb < 0 || pb >= NB) return -2;
+    }
+  }
+  int fail = 0;
+#ifdef _OPENMP
+  if (threads <= 0) threads = omp_get_max_threads();
+#pragma omp parallel for collapse(2) schedule(dynamic, 1) num_threads(threads)
+#endif
+  for (int64_t s = 0; s < S; ++s) {
+    for (int64_t h = 0; h < Hq; ++h) {
+      const int64_t L = context_lens[s];
+      double* o = ref + (s * Hq + h) * D;
+      for (int64_t e = 0; e < D; ++e) o[e] = 0.0;
+      if (L == 0) continue;
+      const int64_t kvh = h / G;
+      const uint16_t* qrow = q + (s * Hq + h) * D;
+      double* x = (double*)malloc(sizeof(double) * (size_t)L);
+      if (!x) { fail = 1; continue; }
+      /* scores */
+      for (int64_t t = 0; t < L; ++t) {
+        const int64_t pb = block_tables[s * MAXB + t / B];
+        const uint16_t* krow = k_pool + ((pb * Hkv + kvh) * B + t % B) * D;
+        double dot = 0.0;
+        for (int64_t d = 0; d < D; ++d) dot += widen_bf16(qrow[d]) * widen_bf16(krow[d]);
+        x[t] = (double)scale * dot;
+      }
+      /* softmax weights */
+      double m = x[0];
+      for (int64_t t = 1; t < L; ++t) if (x[t] > m) m = x[t];
+      double Z = 0.0;
+      for (int64_t t = 0; t < L; ++t) { x[t] = exp(x[t] - m); Z += x[t]; }
+      /* weighted sum of V rows */
+      for (int64_t t = 0; t < L; ++t) {
+        const int64_t pb = block_tables[s * MAXB + t / B];
+        const uint16_t* vrow = v_pool + ((pb * Hkv + kvh) * B + t % B) * D;
+        const double w = x[t] / Z;
+        for (int64_t e = 0; e < D; ++e) o[e] += w * widen_bf16(vrow[e]);
+      }
+      free(x);
+    }
+  }
+  return fail ? -3 : 0;
+}
+
+/* staging[i] = pool[ids[i]], whole pages of block_bytes bytes. */
+int pkv_oracle_kv_blocks_gather(const uint8_t* pool, const int32_t* ids, uint8_t* staging,
+                                int64_t n, int64_t block_bytes, int64_t NB) {
+  if (n < 0 || block_bytes <= 0) return -1;
+  for (int64_t i = 0; i < n; ++i) {
+    if (ids[i] < 0 || ids[i] >= NB) return -2;
+    memcpy(staging + i * block_bytes, pool + (int64_t)ids[i] * block_bytes, (size_t)block_bytes);
+  }
+  return 0;
+}
+
+/* pool[ids[i]] = staging[i]; a page listed twice is an error (-4). */
+int pkv_oracle_kv_blocks_scatter(const uint8_t* staging, uint8_t* pool, const int32_t* ids,
+                                 int64_t n, int64_t block_bytes, int64_t NB) {
+  if (n < 0 || block_bytes <= 0) return -1;
+  uint8_t* seen = (uint8_t*)calloc((size_t)(NB > 0 ? NB : 1), 1);
+  if (!seen) return -3;
+  for (int64_t i = 0; i < n; ++i) {
+    if (ids[i] < 0 || ids[i] >= NB) { free(seen); return -2; }
+    if (seen[ids[i]]) { free(seen); return -4; }
+    seen[ids[i]] = 1;
+  }
+  free(seen);
+  for (int64_t i = 0; i < n; ++i)
+    memcpy(pool + (int64_t)ids[i] * block_bytes, staging + i * block_bytes, (size_t)block_bytes);
+  return 0;
+}

@@ -1,0 +1,290 @@
+"""Seeded synthetic inputs for the paged-decode hot path.
+
+This module only *makes inputs*: context lengths, block tables, block-id lists
+and bf16 bit patterns.  It holds none of the attention or copy arithmetic, so it
+may serve both the HIP path and the CPU checker without coupling them.
+
+The shapes follow the served model named in the paper's evaluation set-up
+(Section V-A: a 32B distilled reasoning model, i.e. 40 query heads, 8 KV heads,
+head_dim 128, 64 layers) and the regime the paper studies: long reasoning
+contexts next to shorter answering ones (Section III), a KV pool that is full
+(Section II-B), and requests whose whole KV cache is evicted or migrated
+(Sections II-B, IV-B).  The paper's own traces are not available; these
+generators stand in for them.
+
+All tensors are numpy arrays; bf16 tensors are ``uint16`` bit patterns.
+"""
+from __future__ import annotations
+
+import math
+from dataclasses import dataclass, field
+from typing import List, Optional, Tuple
+
+import numpy as np
+
+BASE_SEED = 20260211
+HEAD_DIM = 128
+BLOCK_SIZE = 16
+
+
+# --------------------------------------------------------------------------
+# bf16 bit-pattern helpers (marshalling only)
+# --------------------------------------------------------------------------
+def f32_to_bf16_bits(x: np.ndarray) -> np.ndarray:
+    """Round float32 to bf16 (nearest, ties to even); returns uint16 bits.
+
+    Inputs here are finite; NaN payloads are not treated specially.
+    """
+    x = np.ascontiguousarray(x, dtype=np.float32)
+    u = x.view(np.uint32)
+    bias = ((u >> np.uint32(16)) & np.uint32(1)) + np.uint32(0x7FFF)
+    return ((u + bias) >> np.uint32(16)).astype(np.uint16)
+
+
+def bf16_bits_to_f64(bits: np.ndarray) -> np.ndarray:
+    """Widen bf16 bit patterns exactly to float64."""
+    bits = np.ascontiguousarray(bits, dtype=np.uint16)
+    return (bits.astype(np.uint32) << np.uint32(16)).view(np.float32).astype(np.float64)
+
+
+def normal_bf16(rng: np.random.Generator, shape) -> np.ndarray:
+    """bf16 bit patterns of N(0,1) draws (drawn in fp32, rounded once)."""
+    return f32_to_bf16_bits(rng.standard_normal(size=shape, dtype=np.float32))
+
+
+BF16_NAN = np.uint16(0x7FC0)
+BF16_INF = np.uint16(0x7F80)
+
+
+# --------------------------------------------------------------------------
+# Workload descriptions
+# --------------------------------------------------------------------------
+@dataclass
+class Workload:
+    """One batch of decode requests over one or more layers' KV pools."""
+
+    name: str
+    num_q_heads: int
+    num_kv_heads: int
+    context_lens: np.ndarray          # int32 [S]
+    block_tables: np.ndarray          # int32 [S, MAXB], unused entries = -1
+    num_pool_blocks: int              # NB (per pool)
+    num_layers: int = 1
+    partition_size: int = 0           # split-K partition in tokens; 0 = library picks
+    head_dim: int = HEAD_DIM
+    block_size: int = BLOCK_SIZE
+    seed: int = BASE_SEED
+    phase: Optional[np.ndarray] = None  # per request: 1 = reasoning, 0 = answering
+    notes: str = ""
+
+    @property
+    def num_seqs(self) -> int:
+        return int(self.context_lens.shape[0])
+
+    @property
+    def max_blocks_per_seq(self) -> int:
+        return int(self.block_tables.shape[1])
+
+    @property
+    def scale(self) -> np.float32:
+        return np.float32(1.0 / math.sqrt(self.head_dim))
+
+    @property
+    def total_tokens(self) -> int:
+        return int(self.context_lens.astype(np.int64).sum())
+
+    @property
+    def block_elems(self) -> int:
+        """bf16 elements in one physical block of one pool (all KV heads)."""
+        return self.num_kv_heads * self.block_size * self.head_dim
+
+    @property
+    def block_bytes(self) -> int:
+        return 2 * self.block_elems
+
+    def pool_shape(self) -> Tuple[int, int, int, int]:
+        return (self.num_pool_blocks, self.num_kv_heads, self.block_size, self.head_dim)
+
+    def q_shape(self) -> Tuple[int, int, int]:
+        return (self.num_seqs, self.num_q_heads, self.head_dim)
+
+    def used_blocks(self) -> np.ndarray:
+        """Blocks per request actually dereferenced: ceil(L/B)."""
+        return (self.context_lens.astype(np.int64) + self.block_size - 1) // self.block_size
+
+    def attn_algorithmic_bytes(self) -> int:
+        """Bytes one attention call must move: every valid K and V row once
+        (shared by the GQA group), q in, out out, the used table entries and
+        the lengths.  Workspace traffic and partial-block over-fetch are
+        overhead and are not counted."""
+        kv = 2 * self.total_tokens * self.num_kv_heads * self.head_dim * 2
+        qo = 2 * self.num_seqs * self.num_q_heads * self.head_dim * 2
+        tbl = int(self.used_blocks().sum()) * 4 + 4 * self.num_seqs
+        return kv + qo + tbl
+
+
+def _tables_from_perm(lens: np.ndarray, perm: np.ndarray, block_size: int,
+                      maxb: Optional[int] = None, fill: int = -1) -> np.ndarray:
+    nblk = (lens.astype(np.int64) + block_size - 1) // block_size
+    if maxb is None:
+        maxb = int(nblk.max()) if len(nblk) else 1
+        maxb = max(maxb, 1)
+    assert int(nblk.sum()) <= len(perm), "pool too small for the batch"
+    assert int(nblk.max(initial=0)) <= maxb
+    tables = np.full((len(lens), maxb), fill, dtype=np.int32)
+    off = 0
+    for s, n in enumerate(nblk):
+        n = int(n)
+        tables[s, :n] = perm[off:off + n]
+        off += n
+    return tables
+
+
+def make_tables(lens, num_pool_blocks: int, rng: np.random.Generator,
+                block_size: int = BLOCK_SIZE, maxb: Optional[int] = None,
+                fill: int = -1) -> np.ndarray:
+    """Cut a seeded permutation of range(NB) consecutively into table rows."""
+    lens = np.asarray(lens, dtype=np.int32)
+    perm = rng.permutation(num_pool_blocks).astype(np.int32)
+    return _tables_from_perm(lens, perm, block_size, maxb, fill)
+
+
+def custom(lens, num_q_heads: int, num_kv_heads: int, seed: int,
+           num_pool_blocks: Optional[int] = None, maxb: Optional[int] = None,
+           partition_size: int = 0, name: str = "custom", fill: int = -1) -> Workload:
+    """Arbitrary lengths (edge-case sweeps)."""
+    lens = np.asarray(lens, dtype=np.int32)
+    need = int(((lens.astype(np.int64) + BLOCK_SIZE - 1) // BLOCK_SIZE).sum())
+    nb = max(need, 1) if num_pool_blocks is None else num_pool_blocks
+    rng = np.random.default_rng(seed)
+    tables = make_tables(lens, nb, rng, maxb=maxb, fill=fill)
+    return Workload(name, num_q_heads, num_kv_heads, lens, tables, nb,
+                    partition_size=partition_size, seed=seed)
+
+
+def cfg1_tiny(seed: int = BASE_SEED + 1) -> Workload:
+    """Batch 4, 8 query / 2 KV heads, lengths U{17..300}, 128-block pool."""
+    rng = np.random.default_rng(seed)
+    lens = rng.integers(17, 301, size=4).astype(np.int32)
+    tables = make_tables(lens, 128, rng, maxb=19)
+    return Workload("cfg1_tiny", 8, 2, lens, tables, 128, seed=seed)
+
+
+def cfg2_qwen32b(seed: int = BASE_SEED + 2, batch: int = 64,
+                 lo: int = 1024, hi: int = 8192) -> Workload:
+    """Batch 64, 40 query / 8 KV heads, lengths U{1024..8192}; the pool holds
+    exactly the batch and the tables are a shuffle of it."""
+    rng = np.random.default_rng(seed)
+    lens = rng.integers(lo, hi + 1, size=batch).astype(np.int32)
+    nb = int(((lens.astype(np.int64) + BLOCK_SIZE - 1) // BLOCK_SIZE).sum())
+    tables = make_tables(lens, nb, rng, maxb=(hi + BLOCK_SIZE - 1) // BLOCK_SIZE)
+    return Workload("cfg2_qwen32b_b64_u1024_8192", 40, 8, lens, tables, nb, seed=seed)
+
+
+def cfg3_long_cot(seed: int = BASE_SEED + 3, batch: int = 128) -> Workload:
+    """Batch 128, lognormal lengths (median 6000, sigma 0.8 in natural-log
+    units) clipped to [512, 32768], split-K partitions of 512 tokens."""
+    rng = np.random.default_rng(seed)
+    raw = np.exp(rng.normal(math.log(6000.0), 0.8, size=batch))
+    lens = np.clip(np.rint(raw), 512, 32768).astype(np.int32)
+    nb = int(((lens.astype(np.int64) + BLOCK_SIZE - 1) // BLOCK_SIZE).sum())
+    tables = make_tables(lens, nb, rng, maxb=32768 // BLOCK_SIZE)
+    return Workload("cfg3_longcot_b128_lognormal", 40, 8, lens, tables, nb,
+                    partition_size=512, seed=seed)
+
+
+def cfg4_phase_mixed(seed: int = BASE_SEED + 4, batch: int = 96, num_layers: int = 64,
+                     spare_blocks: int = 0) -> Workload:
+    """Batch 96: 70 % reasoning requests (U{4096..16384}) and 30 % answering
+    requests (U{1024..4096}), order shuffled; the same lengths and tables in
+    every layer, one K and one V pool per layer."""
+    rng = np.random.default_rng(seed)
+    n_reason = int(round(0.7 * batch))
+    n_answer = batch - n_reason
+    lens = np.concatenate([
+        rng.integers(4096, 16385, size=n_reason),
+        rng.integers(1024, 4097, size=n_answer),
+    ]).astype(np.int32)
+    phase = np.concatenate([np.ones(n_reason, np.int8), np.zeros(n_answer, np.int8)])
+    order = rng.permutation(batch)
+    lens, phase = lens[order], phase[order]
+    nb = int(((lens.astype(np.int64) + BLOCK_SIZE - 1) // BLOCK_SIZE).sum()) + spare_blocks
+    tables = make_tables(lens, nb, rng, maxb=16384 // BLOCK_SIZE)
+    return Workload("cfg4_phase_mixed_b96", 40, 8, lens, tables, nb,
+                    num_layers=num_layers, seed=seed, phase=phase)
+
+
+@dataclass
+class Migration:
+    """One preemption / phase-boundary migration step over a workload."""
+
+    victims: np.ndarray        # int32 request indices being moved
+    survivors: np.ndarray      # int32 request indices that keep decoding
+    old_ids: np.ndarray        # int32 [n] physical blocks gathered, request-major
+    new_ids: np.ndarray        # int32 [n] blocks the staging image is scattered into
+    tables_after: np.ndarray   # int32 [S, MAXB] block tables after the move
+
+
+def make_migration(w: Workload, frac: float = 0.25, seed: Optional[int] = None) -> Migration:
+    """Pick a seeded fraction of requests as victims.  Their blocks are gathered
+    in request order; the destination ids are a seeded reshuffle of a free list
+    made of the pool's spare blocks plus the victims' own just-vacated blocks
+    (legal because the gather of a pool completes before its scatter)."""
+    seed = w.seed + 5 if seed is None else seed
+    rng = np.random.default_rng(seed)
+    S = w.num_seqs
+    n_v = max(1, int(round(frac * S)))
+    perm = rng.permutation(S)
+    victims = np.sort(perm[:n_v]).astype(np.int32)
+    survivors = np.sort(perm[n_v:]).astype(np.int32)
+    used = w.used_blocks()
+    old = [w.block_tables[s, :int(used[s])] for s in victims]
+    old_ids = np.concatenate(old).astype(np.int32) if old else np.zeros(0, np.int32)
+    in_use = np.zeros(w.num_pool_blocks, dtype=bool)
+    for s in range(S):
+        in_use[w.block_tables[s, :int(used[s])]] = True
+    spare = np.nonzero(~in_use)[0].astype(np.int32)
+    free = np.concatenate([spare, old_ids])
+    new_ids = rng.permutation(free)[:len(old_ids)].astype(np.int32)
+    tables_after = w.block_tables.copy()
+    off = 0
+    for s in victims:
+        n = int(used[s])
+        tables_after[s, :n] = new_ids[off:off + n]
+        off += n
+    return Migration(victims, survivors, old_ids, new_ids, tables_after)
+
+
+def subset(w: Workload, idx) -> Workload:
+    """The same pools seen by a sub-batch (continuous batching changes the
+    batch every step; the pool and the other requests' blocks stay put)."""
+    idx = np.asarray(idx, dtype=np.int64)
+    return Workload(w.name + "_subset", w.num_q_heads, w.num_kv_heads,
+                    np.ascontiguousarray(w.context_lens[idx]),
+                    np.ascontiguousarray(w.block_tables[idx]),
+                    w.num_pool_blocks, num_layers=w.num_layers,
+                    partition_size=w.partition_size, seed=w.seed,
+                    phase=None if w.phase is None else w.phase[idx])
+
+
+def make_host_tensors(w: Workload, layer: int = 0, poison_unused: bool = False):
+    """q, K pool, V pool as bf16 bit patterns (uint16), N(0,1).
+
+    ``poison_unused`` overwrites every slot no request may read (whole unused
+    blocks and the tail slots of each last block) with NaN / Inf patterns."""
+    rng = np.random.default_rng(w.seed + 1000 * layer + 17)
+    q = normal_bf16(rng, w.q_shape())
+    k = normal_bf16(rng, w.pool_shape())
+    v = normal_bf16(rng, w.pool_shape())
+    if poison_unused:
+        valid = np.zeros((w.num_pool_blocks, w.block_size), dtype=bool)
+        used = w.used_blocks()
+        for s in range(w.num_seqs):
+            L = int(w.context_lens[s])
+            for j in range(int(used[s])):
+                n = min(w.block_size, L - j * w.block_size)
+                valid[w.block_tables[s, j], :n] = True
+        mask = ~valid
+        k[mask[:, None, :, None].repeat(w.num_kv_heads, 1).repeat(w.head_dim, 3)] = BF16_NAN
+        v[mask[:, None, :, None].repeat(w.num_kv_heads, 1).repeat(w.head_dim, 3)] = BF16_INF
+    return q, k, v

@@ -1,0 +1,265 @@
+"""CPU-only pins for the fp64 checker: each test ties it to something that is
+not itself — a dense brute force written here in numpy, a library attention
+routine, closed forms and invariances — so that a dropped term, a wrong index or
+a transposed operand in the checker fails at least one of them."""
+import math
+
+import numpy as np
+import pytest
+import torch
+
+import oracle
+from paper_2602_11530_amd import workloads as wl
+
+
+def depage(w, pool, s):
+    """Dense [L, Hkv, D] float64 rows of request s (written independently of the
+    checker: numpy fancy indexing, block-major)."""
+    L = int(w.context_lens[s])
+    nb = (L + w.block_size - 1) // w.block_size
+    blocks = pool[w.block_tables[s, :nb]]                      # [nb, Hkv, B, D]
+    rows = np.transpose(blocks, (0, 2, 1, 3)).reshape(nb * w.block_size, w.num_kv_heads,
+                                                      w.head_dim)[:L]
+    return wl.bf16_bits_to_f64(rows).reshape(L, w.num_kv_heads, w.head_dim)
+
+
+def brute_force(w, q, k, v, scale):
+    """softmax(scale * q K^T) V per request and head, dense numpy fp64."""
+    out = np.zeros(w.q_shape(), dtype=np.float64)
+    G = w.num_q_heads // w.num_kv_heads
+    qf = wl.bf16_bits_to_f64(q).reshape(w.q_shape())
+    for s in range(w.num_seqs):
+        if w.context_lens[s] == 0:
+            continue
+        K = depage(w, k, s)
+        V = depage(w, v, s)
+        for h in range(w.num_q_heads):
+            x = float(np.float32(scale)) * (K[:, h // G, :] @ qf[s, h])
+            p = np.exp(x - x.max())
+            p /= p.sum()
+            out[s, h] = p @ V[:, h // G, :]
+    return out
+
+
+def run(w, q, k, v, scale=None):
+    scale = w.scale if scale is None else scale
+    return oracle.paged_decode_attn(q, k, v, w.block_tables, w.context_lens, scale)
+
+
+def test_bf16_widening_matches_library():
+    bits = np.arange(0, 65536, dtype=np.uint16)
+    finite = ((bits >> 7) & 0xFF) != 0xFF
+    bits = bits[finite]
+    lib = torch.from_numpy(bits.view(np.int16).copy()).view(torch.bfloat16).double().numpy()
+    assert np.array_equal(wl.bf16_bits_to_f64(bits), lib)
+    # the checker's own widening: L = 1 returns V exactly (see below) on every pattern
+    w = wl.custom([1], 1, 1, seed=3)
+    for chunk in np.array_split(bits, len(bits) // 128 + 1):
+        v = np.zeros(w.pool_shape(), np.uint16)
+        v[w.block_tables[0, 0], 0, 0, :len(chunk)] = chunk
+        q = np.zeros(w.q_shape(), np.uint16)
+        got = run(w, q, v, v)
+        assert np.array_equal(got[0, 0, :len(chunk)], wl.bf16_bits_to_f64(chunk))
+
+
+def test_f32_to_bf16_matches_library_rounding():
+    rng = np.random.default_rng(5)
+    x = np.concatenate([rng.standard_normal(20000).astype(np.float32) * 3,
+                        np.array([1.00390625, 1.01171875, -1.00390625, 0.0, 65504.0],
+                                 np.float32)])
+    lib = torch.from_numpy(x).to(torch.bfloat16).view(torch.int16).numpy().view(np.uint16)
+    assert np.array_equal(wl.f32_to_bf16_bits(x), lib)
+
+
+def test_brute_force_tiny_cfg1():
+    w = wl.cfg1_tiny()
+    assert w.num_seqs == 4 and w.num_q_heads == 8 and w.num_kv_heads == 2
+    assert w.context_lens.min() >= 17 and w.context_lens.max() <= 300
+    q, k, v = wl.make_host_tensors(w)
+    ref = run(w, q, k, v)
+    bf = brute_force(w, q, k, v, w.scale)
+    assert np.abs(ref - bf).max() < 1e-12
+
+
+@pytest.mark.parametrize("lens", [[1], [15, 16, 17], [31, 32, 33, 1, 0, 2], [511, 512, 513]])
+def test_brute_force_edge_lengths(lens):
+    w = wl.custom(lens, 10, 2, seed=11, num_pool_blocks=200)
+    q, k, v = wl.make_host_tensors(w, poison_unused=True)
+    ref = run(w, q, k, v)
+    assert np.isfinite(ref).all()
+    bf = brute_force(w, q, k, v, w.scale)
+    assert np.abs(ref - bf).max() < 1e-12
+    for s, L in enumerate(lens):
+        if L == 0:
+            assert not ref[s].any()
+
+
+def test_library_attention_medium():
+    """torch's fp64 scaled_dot_product_attention on de-paged, head-repeated rows."""
+    w = wl.custom([700, 45, 1300], 40, 8, seed=23)
+    q, k, v = wl.make_host_tensors(w)
+    ref = run(w, q, k, v)
+    G = 5
+    qf = torch.from_numpy(wl.bf16_bits_to_f64(q).reshape(w.q_shape()))
+    for s in range(w.num_seqs):
+        K = torch.from_numpy(depage(w, k, s)).repeat_interleave(G, dim=1)   # [L, Hq, D]
+        V = torch.from_numpy(depage(w, v, s)).repeat_interleave(G, dim=1)
+        o = torch.nn.functional.scaled_dot_product_attention(
+            qf[s][:, None, :], K.permute(1, 0, 2), V.permute(1, 0, 2),
+            scale=float(np.float32(w.scale)))
+        assert np.abs(o[:, 0, :].numpy() - ref[s]).max() < 1e-12
+
+
+def test_length_one_returns_v_exactly():
+    w = wl.custom([1, 1, 1], 8, 2, seed=7, num_pool_blocks=50)
+    q, k, v = wl.make_host_tensors(w, poison_unused=True)
+    ref = run(w, q, k, v)
+    for s in range(3):
+        for h in range(8):
+            want = wl.bf16_bits_to_f64(v[w.block_tables[s, 0], h // 4, 0])
+            assert np.array_equal(ref[s, h], want)
+
+
+def test_two_token_closed_form():
+    """Scores ln 2 and 0 give weights 2/3 and 1/3; only head_dim element 0 of q
+    and K is non-zero, so a transposed or mis-strided operand changes the result."""
+    w = wl.custom([2], 2, 1, seed=1)
+    D = w.head_dim
+    pb = int(w.block_tables[0, 0])
+    qf = np.zeros(w.q_shape(), np.float32)
+    kf = np.zeros(w.pool_shape(), np.float32)
+    vf = np.zeros(w.pool_shape(), np.float32)
+    qf[0, 0, 0] = 1.0
+    qf[0, 1, 3] = 2.0
+    kf[pb, 0, 0, 0] = 1.0       # token 0, head 0 sees score scale*1
+    kf[pb, 0, 1, 3] = 1.0       # token 1, head 1 sees score scale*2
+    vf[pb, 0, 0, :] = 3.0
+    vf[pb, 0, 1, :] = -6.0
+    vf[pb, 0, 1, 5] = 12.0
+    scale = np.float32(math.log(2.0))
+    ref = oracle.paged_decode_attn(wl.f32_to_bf16_bits(qf), wl.f32_to_bf16_bits(kf),
+                                   wl.f32_to_bf16_bits(vf), w.block_tables,
+                                   w.context_lens, scale)
+    a = math.exp(float(scale))            # head 0: weights a/(a+1), 1/(a+1)
+    want0 = (a * 3.0 + 1.0 * -6.0) / (a + 1.0)
+    b = math.exp(2.0 * float(scale))      # head 1: weights 1/(1+b), b/(1+b)
+    want1 = (3.0 + b * -6.0) / (1.0 + b)
+    assert abs(ref[0, 0, 1] - want0) < 1e-14 and abs(ref[0, 1, 1] - want1) < 1e-14
+    assert abs(ref[0, 1, 5] - (3.0 + b * 12.0) / (1.0 + b)) < 1e-14
+    assert abs(a - 2.0) < 1e-6            # fp32(ln 2): weights are 2/3, 1/3 to 1e-7
+    assert abs(ref[0, 0, 0] - 0.0) < 1e-6
+
+
+def test_scale_zero_is_mean_and_masks_hold():
+    w = wl.custom([37, 16, 100], 8, 2, seed=9, num_pool_blocks=40)
+    q, k, v = wl.make_host_tensors(w, poison_unused=True)
+    ref = run(w, q, k, v, scale=0.0)
+    for s in range(w.num_seqs):
+        V = depage(w, v, s)
+        for h in range(8):
+            assert np.abs(ref[s, h] - V[:, h // 4, :].mean(0)).max() < 1e-13
+
+
+def test_v_all_ones_gives_ones():
+    """Weights sum to one: with V == 1 every output element is 1."""
+    w = wl.cfg1_tiny()
+    q, k, v = wl.make_host_tensors(w)
+    v[:] = wl.f32_to_bf16_bits(np.ones(1, np.float32))[0]
+    ref = run(w, q, k, v)
+    assert np.abs(ref - 1.0).max() < 1e-14
+
+
+def test_score_shift_invariance():
+    """Adding one vector to every K row shifts all scores of a head alike."""
+    w = wl.custom([90, 33], 4, 2, seed=13)
+    rng = np.random.default_rng(2)
+    # values on a 1/8 grid so that K + c is exact in bf16
+    kf = rng.integers(-16, 17, size=w.pool_shape()).astype(np.float32) / 8
+    cf = rng.integers(-8, 9, size=(w.head_dim,)).astype(np.float32) / 8
+    qf = rng.integers(-8, 9, size=w.q_shape()).astype(np.float32) / 8
+    _, _, v = wl.make_host_tensors(w)
+    a = oracle.paged_decode_attn(wl.f32_to_bf16_bits(qf), wl.f32_to_bf16_bits(kf), v,
+                                 w.block_tables, w.context_lens, w.scale)
+    b = oracle.paged_decode_attn(wl.f32_to_bf16_bits(qf), wl.f32_to_bf16_bits(kf + cf), v,
+                                 w.block_tables, w.context_lens, w.scale)
+    assert np.abs(a - b).max() < 1e-12
+    assert np.abs(a).max() > 1e-3
+
+
+def test_paging_invariance():
+    """Permute the physical blocks and rewrite the tables: identical result."""
+    w = wl.cfg1_tiny()
+    q, k, v = wl.make_host_tensors(w)
+    ref = run(w, q, k, v)
+    rng = np.random.default_rng(99)
+    perm = rng.permutation(w.num_pool_blocks)       # new id of old block i = perm[i]
+    k2, v2 = np.empty_like(k), np.empty_like(v)
+    k2[perm], v2[perm] = k, v
+    t2 = np.where(w.block_tables >= 0, perm[np.clip(w.block_tables, 0, None)], -1).astype(np.int32)
+    ref2 = oracle.paged_decode_attn(q, k2, v2, t2, w.context_lens, w.scale)
+    assert np.array_equal(ref, ref2)
+
+
+def test_gqa_equals_mha_with_repeated_kv():
+    w = wl.cfg1_tiny()
+    q, k, v = wl.make_host_tensors(w)
+    ref = run(w, q, k, v)
+    G = w.num_q_heads // w.num_kv_heads
+    k_rep = np.repeat(k, G, axis=1)
+    v_rep = np.repeat(v, G, axis=1)
+    ref_mha = oracle.paged_decode_attn(q, k_rep, v_rep, w.block_tables, w.context_lens, w.scale)
+    assert np.array_equal(ref, ref_mha)
+
+
+def test_batch_independence():
+    w = wl.cfg1_tiny()
+    q, k, v = wl.make_host_tensors(w)
+    ref = run(w, q, k, v)
+    idx = [2, 0]
+    sub = wl.subset(w, idx)
+    ref_sub = oracle.paged_decode_attn(q[idx], k, v, sub.block_tables, sub.context_lens, w.scale)
+    assert np.array_equal(ref_sub, ref[idx])
+
+
+def test_unused_table_entries_never_read():
+    w = wl.cfg1_tiny()
+    q, k, v = wl.make_host_tensors(w)
+    ref = run(w, q, k, v)
+    t = w.block_tables.copy()
+    t[t < 0] = w.num_pool_blocks + 12345
+    ref2 = oracle.paged_decode_attn(q, k, v, t, w.context_lens, w.scale)
+    assert np.array_equal(ref, ref2)
+    t[0, 0] = w.num_pool_blocks      # a *used* entry out of range is rejected
+    with pytest.raises(ValueError):
+        oracle.paged_decode_attn(q, k, v, t, w.context_lens, w.scale)
+
+
+def test_gather_scatter_against_fancy_indexing():
+    rng = np.random.default_rng(4)
+    pool = rng.integers(0, 65536, size=(50, 2, 16, 128)).astype(np.uint16)
+    ids = rng.permutation(50)[:17].astype(np.int32)
+    st = oracle.kv_blocks_gather(pool, ids)
+    assert np.array_equal(st, pool[ids])
+    new_ids = rng.permutation(50)[:17].astype(np.int32)
+    out = oracle.kv_blocks_scatter(st, pool, new_ids)
+    want = pool.copy()
+    want[new_ids] = st
+    assert np.array_equal(out, want)
+    untouched = np.setdiff1d(np.arange(50), new_ids)
+    assert np.array_equal(out[untouched], pool[untouched])
+    assert oracle.kv_blocks_gather(pool, np.zeros(0, np.int32)).shape[0] == 0
+    with pytest.raises(ValueError):
+        oracle.kv_blocks_scatter(st, pool, np.array([1] * 17, np.int32))
+    with pytest.raises(ValueError):
+        oracle.kv_blocks_gather(pool, np.array([50], np.int32))
+
+
+def test_migration_round_trip_keeps_attention():
+    w = wl.cfg1_tiny()
+    q, k, v = wl.make_host_tensors(w)
+    ref = run(w, q, k, v)
+    mig = wl.make_migration(w, 0.25)
+    k2 = oracle.kv_blocks_scatter(oracle.kv_blocks_gather(k, mig.old_ids), k, mig.new_ids)
+    v2 = oracle.kv_blocks_scatter(oracle.kv_blocks_gather(v, mig.old_ids), v, mig.new_ids)
+    ref2 = oracle.paged_decode_attn(q, k2, v2, mig.tables_after, w.context_lens, w.scale)
+    assert np.array_equal(ref, ref2)
