@@ -1,0 +1,147 @@
+/*
+ * pkv — paged KV-cache decode attention and KV-block migration for MI355X (gfx950).
+ *
+ * C ABI.  Every pointer marked "device" is HIP device memory owned by the
+ * caller; every pointer marked "host" is ordinary host memory read only during
+ * the call.  The library allocates nothing, frees nothing and keeps no state
+ * between calls, so calls on different streams may overlap as long as their
+ * outputs (and workspaces) do not.  Every call validates its host-visible
+ * arguments first, then enqueues its kernels on `stream` and returns without
+ * synchronising.
+ *
+ * Pool layout.  A layer's K pool and V pool are each
+ *     bf16 [num_pool_blocks][num_kv_heads][block_size][head_dim], row-major,
+ * so one physical block is one contiguous image of
+ *     num_kv_heads * block_size * head_dim * 2 bytes  (32 KiB at 8 x 16 x 128).
+ *
+ * Status codes: 0 = PKV_OK; negative = error, nothing was enqueued.
+ */
+#ifndef PKV_H_
+#define PKV_H_
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define PKV_OK 0
+#define PKV_ERR_NULL (-1)      /* a required pointer is NULL                          */
+#define PKV_ERR_SHAPE (-2)     /* unsupported or inconsistent sizes                   */
+#define PKV_ERR_ALIGN (-3)     /* a pointer or byte count is not 16-byte aligned      */
+#define PKV_ERR_WORKSPACE (-4) /* workspace missing or smaller than required          */
+#define PKV_ERR_LAUNCH (-5)    /* HIP refused the launch; see pkv_last_launch_error() */
+
+/* Sizes of one attention call.  The batch changes at every decode step
+ * (continuous batching, paper Section II-B), so nothing here is fixed at
+ * library start-up. */
+typedef struct {
+  int32_t num_seqs;           /* S: requests in this step's batch (0 is allowed)        */
+  int32_t num_q_heads;        /* Hq                                                      */
+  int32_t num_kv_heads;       /* Hkv; Hq % Hkv == 0; query heads h*G..h*G+G-1 share
+                                 KV head h (G = Hq/Hkv, 1 <= G <= 16)                    */
+  int32_t head_dim;           /* D: 128                                                  */
+  int32_t block_size;         /* B: 16 tokens per physical block                         */
+  int32_t max_blocks_per_seq; /* MAXB: row stride of block_tables, >= ceil(L_s/B)        */
+  int32_t partition_size;     /* split-K partition in tokens: a multiple of B in
+                                 [B, 4096], or 0 to let the library choose               */
+  int32_t max_context_len;    /* host upper bound on every context_lens[s]; 0 means
+                                 MAXB*B.  A smaller bound only shrinks the launch;
+                                 a request longer than the bound is attended up to it.   */
+  int64_t num_pool_blocks;    /* NB: physical blocks in k_pool and in v_pool, 1..2^31-1  */
+} pkv_attn_shape;
+
+/* The split-K partition size (tokens) a call with this shape will use:
+ * shape->partition_size if non-zero, else the library's choice.
+ * Returns a negative status on a bad shape. */
+int pkv_attn_partition_size(const pkv_attn_shape* shape /* host */);
+
+/* Bytes of device workspace paged_decode_attn needs for this shape (0 when one
+ * partition covers max_context_len).  `out_bytes` is host memory. */
+int pkv_attn_workspace_bytes(const pkv_attn_shape* shape /* host */, size_t* out_bytes);
+
+/*
+ * Decode-step attention of every request in the batch over its whole paged KV
+ * cache — the memory-bandwidth-bound decoding stage of paper Section II-A,
+ * whose time grows with the KV footprint (Section IV-B, discussion of the
+ * reasoning-placement algorithm):
+ *
+ *   out[s,h,:] = sum_t softmax_t( scale * q[s,h,:] . K[s,t,kvh,:] ) * V[s,t,kvh,:]
+ *   for t in [0, context_lens[s]),   kvh = h / G,
+ *   K[s,t] = k_pool[ block_tables[s][t / B] ][kvh][t % B][:]   (V alike).
+ *
+ * context_lens[s] includes the token being decoded (its K,V row is already in
+ * the pool).  A request with context_lens[s] == 0 gets an all-zero output row.
+ * Table entries at index >= ceil(context_lens[s]/B) and slots past the last
+ * valid token are never read, whatever they hold.  Dereferenced block ids must
+ * lie in [0, num_pool_blocks); the device never follows an id outside that
+ * range (the 16 tokens of such a block are left out of the softmax, so a
+ * corrupt table gives a wrong row, not a memory fault), and a negative
+ * context_lens[s] counts as 0.  Several requests may map the same block.
+ *
+ * Arithmetic: bf16 inputs, fp32 scores, softmax statistics and accumulation,
+ * one round-to-nearest-even to bf16 at the end.  The result does not depend on
+ * which physical blocks hold the rows, nor on the other requests in the batch.
+ *
+ *   q            device  bf16  [S][Hq][D]
+ *   k_pool       device  bf16  [NB][Hkv][B][D]
+ *   v_pool       device  bf16  [NB][Hkv][B][D]
+ *   block_tables device  int32 [S][MAXB]
+ *   context_lens device  int32 [S]
+ *   scale        fp32 softmax scale (1/sqrt(D) for the configs here)
+ *   out          device  bf16  [S][Hq][D], written in full
+ *   shape        host
+ *   workspace    device, >= pkv_attn_workspace_bytes(), 16-byte aligned; may be
+ *                NULL when that size is 0.  Contents need no initialisation and
+ *                are undefined afterwards.
+ *   stream       hipStream_t (NULL = the default stream)
+ */
+int paged_decode_attn(const void* q, const void* k_pool, const void* v_pool,
+                      const int32_t* block_tables, const int32_t* context_lens, float scale,
+                      void* out, const pkv_attn_shape* shape, void* workspace,
+                      size_t workspace_bytes, void* stream);
+
+/*
+ * staging[i] = pool[block_ids[i]] for i in [0, n_blocks): the send side of
+ * evicting a preempted request's KV cache (paper Section II-B) or of shipping
+ * a request's entire KV cache at the reasoning-to-answering transition
+ * (Section IV-B, "KV cache transfer overhead").  Whole blocks move, unused
+ * slots included; the copy is bit-exact.
+ *
+ *   pool       device, num_pool_blocks blocks of block_bytes bytes
+ *   block_ids  device int32 [n_blocks]; an id outside [0, num_pool_blocks) is
+ *              skipped on the device (its staging image is left as it was)
+ *   staging    device, n_blocks * block_bytes bytes, contiguous, must not
+ *              overlap the listed blocks
+ *   block_bytes  multiple of 16
+ *   n_blocks == 0 is a no-op returning PKV_OK.
+ */
+int kv_blocks_gather(const void* pool, const int32_t* block_ids, void* staging,
+                     int64_t n_blocks, int64_t block_bytes, int64_t num_pool_blocks,
+                     void* stream);
+
+/*
+ * pool[block_ids[i]] = staging[i]: the receive side — reloading a resumed
+ * request (Section II-B) or installing a migrated one (Section IV-B) into
+ * freshly allocated blocks.  Ids must be distinct (unchecked); an id outside
+ * [0, num_pool_blocks) is skipped; every pool byte outside the listed blocks is
+ * left untouched.
+ */
+int kv_blocks_scatter(const void* staging, void* pool, const int32_t* block_ids,
+                      int64_t n_blocks, int64_t block_bytes, int64_t num_pool_blocks,
+                      void* stream);
+
+/* Static text for a status code. */
+const char* pkv_status_string(int status);
+
+/* Text of the HIP error behind the calling thread's most recent PKV_ERR_LAUNCH. */
+const char* pkv_last_launch_error(void);
+
+/* ABI version: major * 1000 + minor. */
+int pkv_version(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* PKV_H_ */

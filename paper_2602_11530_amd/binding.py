@@ -1,0 +1,152 @@
+"""Thin ctypes binding over libpkv.so: argument marshalling only.
+
+Function names mirror the C ABI (``include/pkv.h``).  Tensors are torch tensors
+(used purely as device-memory handles); every step of the computation runs in
+the library's HIP kernels.  If the library has not been built the first call
+raises — there is no fallback path.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+from typing import Optional
+
+_PKG = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_PKG, "libpkv.so")
+
+PKV_OK = 0
+PKV_ERR_NULL = -1
+PKV_ERR_SHAPE = -2
+PKV_ERR_ALIGN = -3
+PKV_ERR_WORKSPACE = -4
+PKV_ERR_LAUNCH = -5
+
+EXPORTS = (
+    "pkv_attn_partition_size", "pkv_attn_workspace_bytes", "paged_decode_attn",
+    "kv_blocks_gather", "kv_blocks_scatter", "pkv_status_string",
+    "pkv_last_launch_error", "pkv_version",
+)
+
+
+class AttnShape(ctypes.Structure):
+    """Mirror of ``pkv_attn_shape``."""
+    _fields_ = [
+        ("num_seqs", ctypes.c_int32),
+        ("num_q_heads", ctypes.c_int32),
+        ("num_kv_heads", ctypes.c_int32),
+        ("head_dim", ctypes.c_int32),
+        ("block_size", ctypes.c_int32),
+        ("max_blocks_per_seq", ctypes.c_int32),
+        ("partition_size", ctypes.c_int32),
+        ("max_context_len", ctypes.c_int32),
+        ("num_pool_blocks", ctypes.c_int64),
+    ]
+
+
+class PkvError(RuntimeError):
+    def __init__(self, status: int, text: str):
+        super().__init__(f"pkv status {status}: {text}")
+        self.status = status
+
+
+_lib: Optional[ctypes.CDLL] = None
+
+
+def lib() -> ctypes.CDLL:
+    """The loaded C-ABI library; raises if it is missing."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(LIB_PATH):
+            raise FileNotFoundError(
+                f"{LIB_PATH} is not built; run `python -m paper_2602_11530_amd.build` "
+                "(there is no fallback path)")
+        # PyTorch owns the device memory and the streams this library is handed,
+        # so both must sit on one HIP runtime: load torch (and with it the
+        # runtime it ships) before libpkv.so resolves its own dependency.
+        import torch  # noqa: F401
+        L = ctypes.CDLL(LIB_PATH)
+        vp, i64, i32p = ctypes.c_void_p, ctypes.c_int64, ctypes.c_void_p
+        shp = ctypes.POINTER(AttnShape)
+        L.pkv_version.restype = ctypes.c_int
+        L.pkv_status_string.argtypes = [ctypes.c_int]
+        L.pkv_status_string.restype = ctypes.c_char_p
+        L.pkv_last_launch_error.restype = ctypes.c_char_p
+        L.pkv_attn_partition_size.argtypes = [shp]
+        L.pkv_attn_partition_size.restype = ctypes.c_int
+        L.pkv_attn_workspace_bytes.argtypes = [shp, ctypes.POINTER(ctypes.c_size_t)]
+        L.pkv_attn_workspace_bytes.restype = ctypes.c_int
+        L.paged_decode_attn.argtypes = [vp, vp, vp, i32p, i32p, ctypes.c_float, vp, shp, vp,
+                                        ctypes.c_size_t, vp]
+        L.paged_decode_attn.restype = ctypes.c_int
+        L.kv_blocks_gather.argtypes = [vp, i32p, vp, i64, i64, i64, vp]
+        L.kv_blocks_gather.restype = ctypes.c_int
+        L.kv_blocks_scatter.argtypes = [vp, vp, i32p, i64, i64, i64, vp]
+        L.kv_blocks_scatter.restype = ctypes.c_int
+        _lib = L
+    return _lib
+
+
+def _check(status: int) -> None:
+    if status != PKV_OK:
+        L = lib()
+        text = L.pkv_status_string(status).decode()
+        if status == PKV_ERR_LAUNCH:
+            text += ": " + L.pkv_last_launch_error().decode()
+        raise PkvError(status, text)
+
+
+def _ptr(t) -> Optional[int]:
+    return None if t is None else int(t.data_ptr())
+
+
+def _stream(stream) -> Optional[int]:
+    if stream is None:
+        import torch
+        stream = torch.cuda.current_stream()
+    h = int(getattr(stream, "cuda_stream", stream))
+    return h or None
+
+
+def pkv_version() -> int:
+    return int(lib().pkv_version())
+
+
+def make_shape(num_seqs, num_q_heads, num_kv_heads, max_blocks_per_seq, num_pool_blocks,
+               head_dim=128, block_size=16, partition_size=0, max_context_len=0) -> AttnShape:
+    return AttnShape(num_seqs, num_q_heads, num_kv_heads, head_dim, block_size,
+                     max_blocks_per_seq, partition_size, max_context_len, num_pool_blocks)
+
+
+def pkv_attn_partition_size(shape: AttnShape) -> int:
+    p = lib().pkv_attn_partition_size(ctypes.byref(shape))
+    if p < 0:
+        _check(p)
+    return int(p)
+
+
+def pkv_attn_workspace_bytes(shape: AttnShape) -> int:
+    n = ctypes.c_size_t(0)
+    _check(lib().pkv_attn_workspace_bytes(ctypes.byref(shape), ctypes.byref(n)))
+    return int(n.value)
+
+
+def paged_decode_attn(q, k_pool, v_pool, block_tables, context_lens, scale, out,
+                      shape: AttnShape, workspace=None, stream=None) -> None:
+    """Enqueue one batched decode-attention call; see ``include/pkv.h``."""
+    ws_bytes = 0 if workspace is None else workspace.numel() * workspace.element_size()
+    _check(lib().paged_decode_attn(_ptr(q), _ptr(k_pool), _ptr(v_pool), _ptr(block_tables),
+                                   _ptr(context_lens), ctypes.c_float(scale), _ptr(out),
+                                   ctypes.byref(shape), _ptr(workspace), ws_bytes,
+                                   _stream(stream)))
+
+
+def kv_blocks_gather(pool, block_ids, staging, n_blocks: int, block_bytes: int,
+                     num_pool_blocks: int, stream=None) -> None:
+    _check(lib().kv_blocks_gather(_ptr(pool), _ptr(block_ids), _ptr(staging), n_blocks,
+                                  block_bytes, num_pool_blocks, _stream(stream)))
+
+
+def kv_blocks_scatter(staging, pool, block_ids, n_blocks: int, block_bytes: int,
+                      num_pool_blocks: int, stream=None) -> None:
+    _check(lib().kv_blocks_scatter(_ptr(staging), _ptr(pool), _ptr(block_ids), n_blocks,
+                                   block_bytes, num_pool_blocks, _stream(stream)))

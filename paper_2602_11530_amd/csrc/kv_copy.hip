@@ -1,0 +1,60 @@
+// KV-block gather / scatter for gfx950: whole physical blocks move between a
+// paged pool and a contiguous staging image (eviction / reload of a preempted
+// request, paper Section II-B; whole-cache migration at the phase boundary,
+// Section IV-B).  Pure 16-byte loads and stores, no arithmetic: bit-exact.
+#include "pkv_kernels.h"
+
+namespace pkv {
+namespace {
+
+constexpr int kCopyThreads = 256;
+constexpr int kChunksPerThread = 8;                               // 16-byte chunks
+constexpr int kChunksPerGroup = kCopyThreads * kChunksPerThread;  // 32 KiB per workgroup
+
+// blockIdx.x = index into block_ids, blockIdx.y = 32 KiB slice of that block.
+// The physical id is wave-uniform, so the pool-side base address is scalar;
+// byte offsets are 64-bit (a pool passes 2 GiB at the long-context sizes).
+template <bool kGather>
+__global__ __launch_bounds__(kCopyThreads) void kv_block_copy_kernel(
+    const u32x4* __restrict__ src, u32x4* __restrict__ dst, const int32_t* __restrict__ block_ids,
+    int64_t chunks_per_block, int64_t num_pool_blocks) {
+  const int64_t i = blockIdx.x;
+  const int64_t phys = block_ids[i];
+  if (phys < 0 || phys >= num_pool_blocks) return;   // never follow a corrupt id
+  const int64_t pool_base = phys * chunks_per_block;
+  const int64_t stage_base = i * chunks_per_block;
+  const u32x4* s = src + (kGather ? pool_base : stage_base);
+  u32x4* d = dst + (kGather ? stage_base : pool_base);
+  const int64_t c0 = (int64_t)blockIdx.y * kChunksPerGroup + threadIdx.x;
+  u32x4 v[kChunksPerThread];
+#pragma unroll
+  for (int u = 0; u < kChunksPerThread; ++u) {
+    const int64_t c = c0 + (int64_t)u * kCopyThreads;
+    if (c < chunks_per_block) v[u] = __builtin_nontemporal_load(s + c);
+  }
+#pragma unroll
+  for (int u = 0; u < kChunksPerThread; ++u) {
+    const int64_t c = c0 + (int64_t)u * kCopyThreads;
+    if (c < chunks_per_block) __builtin_nontemporal_store(v[u], d + c);
+  }
+}
+
+}  // namespace
+
+hipError_t launch_kv_block_copy(const void* src, void* dst, const int32_t* block_ids,
+                                int64_t n_blocks, int64_t block_bytes, int64_t num_pool_blocks,
+                                bool gather, hipStream_t stream) {
+  const int64_t chunks = block_bytes / 16;
+  const int64_t slices = (chunks + kChunksPerGroup - 1) / kChunksPerGroup;
+  // grid.x carries the block list (up to 2^31-1), grid.y the slices of a block.
+  dim3 grid((unsigned)n_blocks, (unsigned)slices, 1);
+  if (gather)
+    hipLaunchKernelGGL(kv_block_copy_kernel<true>, grid, dim3(kCopyThreads), 0, stream,
+                       (const u32x4*)src, (u32x4*)dst, block_ids, chunks, num_pool_blocks);
+  else
+    hipLaunchKernelGGL(kv_block_copy_kernel<false>, grid, dim3(kCopyThreads), 0, stream,
+                       (const u32x4*)src, (u32x4*)dst, block_ids, chunks, num_pool_blocks);
+  return hipGetLastError();
+}
+
+}  // namespace pkv

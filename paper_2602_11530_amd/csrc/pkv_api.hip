@@ -1,0 +1,177 @@
+// C-ABI layer of libpkv: argument validation (all of it before any launch, so
+// it can be exercised without a GPU), launch geometry, status codes.
+#include "../../include/pkv.h"
+
+#include "pkv_kernels.h"
+
+namespace {
+
+thread_local hipError_t g_last_launch_error = hipSuccess;
+
+inline bool misaligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) != 0; }
+
+// Library's split-K partition choice when the caller leaves it open: small
+// enough that (requests x KV heads x partitions) oversubscribes 256 CUs several
+// times at batch sizes of a few dozen, large enough that the per-partition
+// epilogue (a 520-byte row per query head) stays near 1 % of the KV it stands for.
+constexpr int kDefaultPartition = 256;
+
+struct Geometry {
+  int G, P, NP, max_ctx;
+};
+
+int check_shape(const pkv_attn_shape* sh, Geometry* g) {
+  if (!sh) return PKV_ERR_NULL;
+  if (sh->num_seqs < 0 || sh->num_q_heads <= 0 || sh->num_kv_heads <= 0) return PKV_ERR_SHAPE;
+  if (sh->head_dim != pkv::kHeadDim || sh->block_size != pkv::kBlockTokens) return PKV_ERR_SHAPE;
+  if (sh->num_q_heads % sh->num_kv_heads != 0) return PKV_ERR_SHAPE;
+  const int G = sh->num_q_heads / sh->num_kv_heads;
+  if (G > 8) return PKV_ERR_SHAPE;
+  if (sh->max_blocks_per_seq <= 0) return PKV_ERR_SHAPE;
+  if ((int64_t)sh->max_blocks_per_seq * pkv::kBlockTokens > INT32_MAX) return PKV_ERR_SHAPE;
+  const int cap = sh->max_blocks_per_seq * pkv::kBlockTokens;
+  if (sh->max_context_len < 0 || sh->max_context_len > cap) return PKV_ERR_SHAPE;
+  const int max_ctx = sh->max_context_len ? sh->max_context_len : cap;
+  int P = sh->partition_size;
+  if (P < 0) return PKV_ERR_SHAPE;
+  if (P == 0) P = kDefaultPartition;
+  if (P % pkv::kBlockTokens != 0 || P < pkv::kBlockTokens || P > pkv::kMaxPartition)
+    return PKV_ERR_SHAPE;
+  if (sh->num_pool_blocks < 1 || sh->num_pool_blocks > INT32_MAX) return PKV_ERR_SHAPE;
+  const int NP = (max_ctx + P - 1) / P;
+  if ((int64_t)sh->num_seqs * NP > INT32_MAX) return PKV_ERR_SHAPE;
+  if ((int64_t)sh->num_seqs * sh->num_q_heads > INT32_MAX) return PKV_ERR_SHAPE;
+  g->G = G;
+  g->P = P;
+  g->NP = NP;
+  g->max_ctx = max_ctx;
+  return PKV_OK;
+}
+
+size_t workspace_bytes(const pkv_attn_shape* sh, const Geometry& g) {
+  if (g.NP <= 1) return 0;
+  const size_t rows = (size_t)sh->num_seqs * g.NP * sh->num_q_heads;
+  return rows * (pkv::kHeadDim * sizeof(float) + sizeof(float2));
+}
+
+int launch_status(hipError_t e) {
+  if (e == hipSuccess) return PKV_OK;
+  g_last_launch_error = e;
+  return PKV_ERR_LAUNCH;
+}
+
+}  // namespace
+
+extern "C" {
+
+int pkv_version(void) { return 1000; }
+
+const char* pkv_status_string(int status) {
+  switch (status) {
+    case PKV_OK: return "ok";
+    case PKV_ERR_NULL: return "a required pointer is NULL";
+    case PKV_ERR_SHAPE: return "unsupported or inconsistent sizes";
+    case PKV_ERR_ALIGN: return "a pointer or byte count is not 16-byte aligned";
+    case PKV_ERR_WORKSPACE: return "workspace missing or too small";
+    case PKV_ERR_LAUNCH: return "HIP refused the launch";
+    default: return "unknown status";
+  }
+}
+
+const char* pkv_last_launch_error(void) { return hipGetErrorString(g_last_launch_error); }
+
+int pkv_attn_partition_size(const pkv_attn_shape* shape) {
+  Geometry g;
+  const int rc = check_shape(shape, &g);
+  return rc != PKV_OK ? rc : g.P;
+}
+
+int pkv_attn_workspace_bytes(const pkv_attn_shape* shape, size_t* out_bytes) {
+  if (!out_bytes) return PKV_ERR_NULL;
+  Geometry g;
+  const int rc = check_shape(shape, &g);
+  if (rc != PKV_OK) return rc;
+  *out_bytes = workspace_bytes(shape, g);
+  return PKV_OK;
+}
+
+int paged_decode_attn(const void* q, const void* k_pool, const void* v_pool,
+                      const int32_t* block_tables, const int32_t* context_lens, float scale,
+                      void* out, const pkv_attn_shape* shape, void* workspace,
+                      size_t workspace_bytes_given, void* stream) {
+  Geometry g;
+  const int rc = check_shape(shape, &g);
+  if (rc != PKV_OK) return rc;
+  if (shape->num_seqs == 0) return PKV_OK;
+  if (!q || !k_pool || !v_pool || !block_tables || !context_lens || !out) return PKV_ERR_NULL;
+  if (misaligned16(q) || misaligned16(k_pool) || misaligned16(v_pool) || misaligned16(out) ||
+      (reinterpret_cast<uintptr_t>(block_tables) & 3u) || (reinterpret_cast<uintptr_t>(context_lens) & 3u))
+    return PKV_ERR_ALIGN;
+  const size_t need = workspace_bytes(shape, g);
+  if (need) {
+    if (!workspace || workspace_bytes_given < need) return PKV_ERR_WORKSPACE;
+    if (misaligned16(workspace)) return PKV_ERR_ALIGN;
+  }
+
+  pkv::AttnLaunch a;
+  a.q = static_cast<const uint16_t*>(q);
+  a.k_pool = static_cast<const uint16_t*>(k_pool);
+  a.v_pool = static_cast<const uint16_t*>(v_pool);
+  a.block_tables = block_tables;
+  a.context_lens = context_lens;
+  a.out = static_cast<uint16_t*>(out);
+  a.S = shape->num_seqs;
+  a.Hq = shape->num_q_heads;
+  a.Hkv = shape->num_kv_heads;
+  a.G = g.G;
+  a.MAXB = shape->max_blocks_per_seq;
+  a.P = g.P;
+  a.NP = g.NP;
+  a.max_ctx = g.max_ctx;
+  a.NB = (int)shape->num_pool_blocks;
+  a.scale_log2e = scale * 1.4426950408889634f;
+  const size_t rows = (size_t)a.S * a.NP * a.Hq;
+  a.ws_acc = static_cast<float*>(workspace);
+  a.ws_ml = need ? reinterpret_cast<float2*>(static_cast<float*>(workspace) + rows * pkv::kHeadDim)
+                 : nullptr;
+
+  hipStream_t st = static_cast<hipStream_t>(stream);
+  hipError_t e = pkv::launch_attn_partition(a, st);
+  if (e != hipSuccess) return launch_status(e);
+  if (a.NP > 1) {
+    e = pkv::launch_attn_reduce(a, st);
+    if (e != hipSuccess) return launch_status(e);
+  }
+  return PKV_OK;
+}
+
+static int copy_call(const void* pool, const void* staging, const int32_t* block_ids,
+                     int64_t n_blocks, int64_t block_bytes, int64_t num_pool_blocks, bool gather,
+                     void* stream) {
+  if (n_blocks < 0 || block_bytes <= 0 || num_pool_blocks < 0) return PKV_ERR_SHAPE;
+  if (block_bytes % 16 != 0) return PKV_ERR_ALIGN;
+  if (n_blocks > INT32_MAX || (block_bytes / 16 + 2047) / 2048 > 65535) return PKV_ERR_SHAPE;
+  if (n_blocks == 0) return PKV_OK;
+  if (!pool || !staging || !block_ids) return PKV_ERR_NULL;
+  if (misaligned16(pool) || misaligned16(staging) || (reinterpret_cast<uintptr_t>(block_ids) & 3u))
+    return PKV_ERR_ALIGN;
+  hipStream_t st = static_cast<hipStream_t>(stream);
+  const hipError_t e =
+      gather ? pkv::launch_kv_block_copy(pool, const_cast<void*>(staging), block_ids, n_blocks,
+                                         block_bytes, num_pool_blocks, true, st)
+             : pkv::launch_kv_block_copy(staging, const_cast<void*>(pool), block_ids, n_blocks,
+                                         block_bytes, num_pool_blocks, false, st);
+  return launch_status(e);
+}
+
+int kv_blocks_gather(const void* pool, const int32_t* block_ids, void* staging, int64_t n_blocks,
+                     int64_t block_bytes, int64_t num_pool_blocks, void* stream) {
+  return copy_call(pool, staging, block_ids, n_blocks, block_bytes, num_pool_blocks, true, stream);
+}
+
+int kv_blocks_scatter(const void* staging, void* pool, const int32_t* block_ids, int64_t n_blocks,
+                      int64_t block_bytes, int64_t num_pool_blocks, void* stream) {
+  return copy_call(pool, staging, block_ids, n_blocks, block_bytes, num_pool_blocks, false, stream);
+}
+
+}  // extern "C"

@@ -1,0 +1,91 @@
+"""Helpers for the GPU parity tests: upload, call through the C ABI, download."""
+import numpy as np
+import torch
+
+from paper_2602_11530_amd import binding as pkv
+from paper_2602_11530_amd import workloads as wl
+
+# Tolerance of the attention parity bar (bf16 in/out, fp32 accumulate).
+MAX_ABS = 1e-2
+REL_L2 = 5e-3
+
+
+def to_dev(a: np.ndarray, device="cuda:0") -> torch.Tensor:
+    """uint16 bit patterns travel as int16; int32 as is."""
+    a = np.ascontiguousarray(a)
+    if a.dtype == np.uint16:
+        a = a.view(np.int16)
+    return torch.from_numpy(a).to(device)
+
+
+def to_bits(t: torch.Tensor) -> np.ndarray:
+    if t.dtype == torch.bfloat16:
+        t = t.view(torch.int16)
+    return t.cpu().numpy().view(np.uint16)
+
+
+def shape_of(w: wl.Workload, partition_size=None, max_context_len=None):
+    P = w.partition_size if partition_size is None else partition_size
+    mc = 0 if max_context_len is None else max_context_len
+    return pkv.make_shape(w.num_seqs, w.num_q_heads, w.num_kv_heads, w.max_blocks_per_seq,
+                          w.num_pool_blocks, w.head_dim, w.block_size, P, mc)
+
+
+def assert_launchable(w: wl.Workload, k_pool=None):
+    """Host-side check, before any launch, that the tables and lengths describe
+    memory the kernels may touch."""
+    assert w.block_tables.dtype == np.int32 and w.context_lens.dtype == np.int32
+    assert w.block_tables.shape == (w.num_seqs, w.max_blocks_per_seq)
+    used = w.used_blocks()
+    assert (w.context_lens >= 0).all() and (used <= w.max_blocks_per_seq).all()
+    for s in range(w.num_seqs):
+        row = w.block_tables[s, :int(used[s])]
+        assert ((row >= 0) & (row < w.num_pool_blocks)).all(), f"request {s}: bad block id"
+    if k_pool is not None:
+        assert tuple(k_pool.shape) == w.pool_shape()
+
+
+def run_attn_dev(w, q_d, k_d, v_d, tables_d, lens_d, partition_size=None,
+                 max_context_len=None, scale=None, stream=None, out=None, workspace=None,
+                 check_tables=True):
+    """Device tensors in, device int16 [S,Hq,D] out (bf16 bits)."""
+    if check_tables:
+        assert_launchable(w, k_d)
+    assert tuple(q_d.shape) == w.q_shape() and tuple(v_d.shape) == w.pool_shape()
+    assert tuple(tables_d.shape) == w.block_tables.shape and tuple(lens_d.shape) == (w.num_seqs,)
+    shape = shape_of(w, partition_size, max_context_len)
+    nbytes = pkv.pkv_attn_workspace_bytes(shape)
+    if workspace is None and nbytes:
+        workspace = torch.empty(nbytes, dtype=torch.uint8, device=q_d.device)
+    if out is None:
+        # poison the output so that rows the kernel fails to write are caught
+        out = torch.full(w.q_shape(), 0x7FC1, dtype=torch.int16, device=q_d.device)
+    pkv.paged_decode_attn(q_d, k_d, v_d, tables_d, lens_d,
+                          float(w.scale if scale is None else scale), out, shape,
+                          workspace, stream)
+    return out
+
+
+def run_attn(w, q, k, v, **kw) -> np.ndarray:
+    """Host bit patterns in, host uint16 [S,Hq,D] out."""
+    dev = [to_dev(x) for x in (q, k, v, w.block_tables, w.context_lens)]
+    out = run_attn_dev(w, *dev, **kw)
+    torch.cuda.synchronize()
+    return to_bits(out)
+
+
+def device_tensors(w: wl.Workload, layer: int = 0, device="cuda:0"):
+    """Seeded N(0,1) bf16 q / K pool / V pool made on the device (large configs)."""
+    g = torch.Generator(device=device)
+    g.manual_seed(w.seed + 1000 * layer + 17)
+    q = torch.randn(w.q_shape(), generator=g, device=device, dtype=torch.float32).to(torch.bfloat16)
+    pools = []
+    for _ in range(2):
+        p = torch.empty(w.pool_shape(), dtype=torch.bfloat16, device=device)
+        flat = p.view(-1)
+        step = 1 << 28
+        for o in range(0, flat.numel(), step):
+            n = min(step, flat.numel() - o)
+            flat[o:o + n] = torch.randn(n, generator=g, device=device, dtype=torch.float32)
+        pools.append(p)
+    return q, pools[0], pools[1]

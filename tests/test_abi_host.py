@@ -1,0 +1,104 @@
+"""CPU-only checks of the C-ABI layer: the library loads, exports every symbol
+the header declares, and rejects bad arguments before touching a device."""
+import ctypes
+import os
+import re
+
+import pytest
+
+from paper_2602_11530_amd import binding as pkv
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def declared_symbols():
+    text = open(os.path.join(ROOT, "include", "pkv.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return set(re.findall(r"\b([a-z_][a-z0-9_]*)\s*\(", text)) - {"defined"}
+
+
+def test_exports_match_header():
+    L = pkv.lib()
+    syms = declared_symbols()
+    assert syms == set(pkv.EXPORTS)
+    for s in syms:
+        assert getattr(L, s) is not None
+    assert pkv.pkv_version() >= 1000
+
+
+def test_shape_struct_layout():
+    assert ctypes.sizeof(pkv.AttnShape) == 40 and pkv.AttnShape.num_pool_blocks.offset == 32
+
+
+def test_status_strings():
+    L = pkv.lib()
+    seen = {L.pkv_status_string(c) for c in range(0, -6, -1)}
+    assert len(seen) == 6 and b"unknown status" not in seen
+    assert L.pkv_status_string(-99) == b"unknown status"
+
+
+def test_partition_and_workspace():
+    sh = pkv.make_shape(128, 40, 8, 2048, 70000, partition_size=512)
+    assert pkv.pkv_attn_partition_size(sh) == 512
+    rows = 128 * 64 * 40
+    assert pkv.pkv_attn_workspace_bytes(sh) == rows * (128 * 4 + 8)
+    sh.max_context_len = 512
+    assert pkv.pkv_attn_workspace_bytes(sh) == 0
+    sh = pkv.make_shape(4, 8, 2, 19, 128)
+    P = pkv.pkv_attn_partition_size(sh)
+    assert P % 16 == 0 and 16 <= P <= 4096
+
+
+@pytest.mark.parametrize("kw", [
+    dict(head_dim=64), dict(block_size=32), dict(num_q_heads=9), dict(num_kv_heads=0),
+    dict(partition_size=24), dict(partition_size=8192), dict(partition_size=-16),
+    dict(max_blocks_per_seq=0), dict(num_seqs=-1), dict(max_context_len=20 * 16),
+    dict(max_context_len=-1), dict(num_pool_blocks=0), dict(num_pool_blocks=2 ** 31),
+])
+def test_bad_shapes(kw):
+    base = dict(num_seqs=4, num_q_heads=8, num_kv_heads=2, max_blocks_per_seq=19,
+                num_pool_blocks=128)
+    base.update(kw)
+    sh = pkv.make_shape(**base)
+    with pytest.raises(pkv.PkvError) as e:
+        pkv.pkv_attn_workspace_bytes(sh)
+    assert e.value.status == pkv.PKV_ERR_SHAPE
+    L = pkv.lib()
+    rc = L.paged_decode_attn(16, 16, 16, 16, 16, 1.0, 16, ctypes.byref(sh), None, 0, None)
+    assert rc == pkv.PKV_ERR_SHAPE
+
+
+def test_attn_argument_errors_before_launch():
+    L = pkv.lib()
+    sh = pkv.make_shape(4, 8, 2, 19, 128, partition_size=16)
+    need = pkv.pkv_attn_workspace_bytes(sh)
+    assert need > 0
+    call = lambda *a: L.paged_decode_attn(*a)
+    assert call(None, 16, 16, 16, 16, 1.0, 16, ctypes.byref(sh), 16, need, None) == pkv.PKV_ERR_NULL
+    assert call(16, 16, 16, 16, 16, 1.0, None, ctypes.byref(sh), 16, need, None) == pkv.PKV_ERR_NULL
+    assert call(16, 16, 16, 16, 16, 1.0, 16, None, 16, need, None) == pkv.PKV_ERR_NULL
+    assert call(24, 16, 16, 16, 16, 1.0, 16, ctypes.byref(sh), 16, need, None) == pkv.PKV_ERR_ALIGN
+    assert call(16, 16, 16, 18, 16, 1.0, 16, ctypes.byref(sh), 16, need, None) == pkv.PKV_ERR_ALIGN
+    assert call(16, 16, 16, 16, 16, 1.0, 16, ctypes.byref(sh), None, need, None) == pkv.PKV_ERR_WORKSPACE
+    assert call(16, 16, 16, 16, 16, 1.0, 16, ctypes.byref(sh), 16, need - 1, None) == pkv.PKV_ERR_WORKSPACE
+    assert call(16, 16, 16, 16, 16, 1.0, 16, ctypes.byref(sh), 24, need, None) == pkv.PKV_ERR_ALIGN
+    sh0 = pkv.make_shape(0, 8, 2, 19, 128)
+    assert call(None, None, None, None, None, 1.0, None, ctypes.byref(sh0), None, 0, None) == pkv.PKV_OK
+
+
+def test_copy_argument_errors_before_launch():
+    L = pkv.lib()
+    for fn, args in ((L.kv_blocks_gather, lambda a, b, c: (a, b, c)),
+                     (L.kv_blocks_scatter, lambda a, b, c: (c, a, b))):
+        # (pool, ids, staging) reordered per entry point
+        assert fn(*args(16, 16, 16), 0, 32768, 64, None) == pkv.PKV_OK
+        assert fn(*args(None, None, None), 0, 32768, 64, None) == pkv.PKV_OK
+        assert fn(*args(16, 16, 16), -1, 32768, 64, None) == pkv.PKV_ERR_SHAPE
+        assert fn(*args(16, 16, 16), 4, 0, 64, None) == pkv.PKV_ERR_SHAPE
+        assert fn(*args(16, 16, 16), 4, 32768, -1, None) == pkv.PKV_ERR_SHAPE
+        assert fn(*args(16, 16, 16), 4, 40, 64, None) == pkv.PKV_ERR_ALIGN
+        assert fn(*args(None, 16, 16), 4, 32768, 64, None) == pkv.PKV_ERR_NULL
+        assert fn(*args(16, None, 16), 4, 32768, 64, None) == pkv.PKV_ERR_NULL
+        assert fn(*args(16, 16, None), 4, 32768, 64, None) == pkv.PKV_ERR_NULL
+        assert fn(*args(24, 16, 16), 4, 32768, 64, None) == pkv.PKV_ERR_ALIGN
+        assert fn(*args(16, 18, 16), 4, 32768, 64, None) == pkv.PKV_ERR_ALIGN

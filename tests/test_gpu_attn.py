@@ -1,0 +1,206 @@
+"""GPU parity of paged_decode_attn (through the C ABI) against the fp64 checker.
+
+Bar: max-abs <= 1e-2 and relative L2 <= 5e-3 over each call's whole output
+(bf16 in/out, fp32 accumulate)."""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+from paper_2602_11530_amd import workloads as wl
+
+from gpu_util import MAX_ABS, REL_L2, device_tensors, run_attn, run_attn_dev, to_bits, to_dev
+
+pytestmark = pytest.mark.gpu
+
+
+def check(w, q, k, v, got, what=""):
+    ref = oracle.paged_decode_attn(q, k, v, w.block_tables, w.context_lens, w.scale)
+    c = oracle.compare(got, ref)
+    print(f"{w.name} {what}: {c}", flush=True)
+    assert np.isfinite(wl.bf16_bits_to_f64(got)).all(), "non-finite output"
+    assert c["max_abs"] <= MAX_ABS and c["rel_l2"] <= REL_L2, c
+    # no single short request may hide in the batch
+    assert c["worst_seq_rel_l2"] <= 2 * REL_L2, c
+    return ref
+
+
+@pytest.mark.parametrize("poison", [False, True])
+def test_cfg1_tiny(device, poison):
+    w = wl.cfg1_tiny()
+    q, k, v = wl.make_host_tensors(w, poison_unused=poison)
+    check(w, q, k, v, run_attn(w, q, k, v), f"poison={poison}")
+
+
+EDGE = [1, 15, 16, 17, 31, 32, 33, 0, 255, 256, 257, 511, 512, 513, 2, 1000]
+
+
+@pytest.mark.parametrize("hq,hkv", [(8, 2), (40, 8), (5, 1), (8, 8), (6, 2), (16, 2)])
+@pytest.mark.parametrize("P", [0, 16, 512])
+def test_edge_lengths(device, hq, hkv, P):
+    w = wl.custom(EDGE, hq, hkv, seed=31 + hq, num_pool_blocks=400, partition_size=P)
+    q, k, v = wl.make_host_tensors(w, poison_unused=True)
+    got = run_attn(w, q, k, v)
+    check(w, q, k, v, got, f"hq={hq} hkv={hkv} P={P}")
+    zero_rows = got.reshape(w.q_shape())[EDGE.index(0)]
+    assert not zero_rows.any(), "an empty request must get an all-zero row"
+
+
+def test_quantum_and_demotion_lengths(device):
+    """Lengths around the scheduler's token quantum (500) and demotion threshold
+    (5000 tokens) of the paper's evaluation set-up (Section V-A)."""
+    w = wl.custom([499, 500, 501, 4999, 5000, 5001], 40, 8, seed=77, partition_size=512)
+    q, k, v = wl.make_host_tensors(w, poison_unused=True)
+    check(w, q, k, v, run_attn(w, q, k, v))
+
+
+def test_partition_size_invariance(device):
+    w = wl.custom([1300, 700, 45, 2048], 40, 8, seed=5)
+    q, k, v = wl.make_host_tensors(w)
+    outs = {}
+    for P in (16, 128, 512, 4096, 0):
+        outs[P] = run_attn(w, q, k, v, partition_size=P)
+        check(w, q, k, v, outs[P], f"P={P}")
+    a = wl.bf16_bits_to_f64(outs[16])
+    for P, o in outs.items():
+        d = wl.bf16_bits_to_f64(o) - a
+        assert np.sqrt((d * d).sum() / (a * a).sum()) <= REL_L2
+
+
+def test_max_context_len_hint_only_shrinks_launch(device):
+    w = wl.custom([300, 90, 17], 8, 2, seed=8, maxb=64, partition_size=64)
+    q, k, v = wl.make_host_tensors(w)
+    full = run_attn(w, q, k, v)
+    hinted = run_attn(w, q, k, v, max_context_len=304)
+    assert np.array_equal(full, hinted)
+
+
+def test_length_one_is_v_bit_exact(device):
+    w = wl.custom([1, 1, 1, 1], 40, 8, seed=3, num_pool_blocks=64)
+    q, k, v = wl.make_host_tensors(w, poison_unused=True)
+    got = run_attn(w, q, k, v).reshape(w.q_shape())
+    for s in range(4):
+        for h in range(40):
+            assert np.array_equal(got[s, h], v[w.block_tables[s, 0], h // 5, 0])
+
+
+def test_v_ones_gives_exact_ones(device):
+    """The softmax weights sum to one."""
+    w = wl.custom([700, 33, 16, 1234], 40, 8, seed=4)
+    q, k, v = wl.make_host_tensors(w)
+    v[:] = 0x3F80
+    for P in (0, 128):
+        got = run_attn(w, q, k, v, partition_size=P)
+        assert (got == 0x3F80).all()
+
+
+def test_scale_zero_is_mean(device):
+    w = wl.custom([37, 16, 100, 600], 8, 2, seed=9, num_pool_blocks=80)
+    q, k, v = wl.make_host_tensors(w, poison_unused=True)
+    got = run_attn(w, q, k, v, scale=0.0)
+    ref = oracle.paged_decode_attn(q, k, v, w.block_tables, w.context_lens, 0.0)
+    c = oracle.compare(got, ref)
+    assert c["max_abs"] <= MAX_ABS and c["rel_l2"] <= REL_L2, c
+
+
+def test_paging_invariance_bitwise(device):
+    """Moving rows to other physical blocks (tables rewritten) changes nothing:
+    the reduction order depends on logical positions only."""
+    w = wl.custom([300, 1000, 77], 40, 8, seed=12, num_pool_blocks=200)
+    q, k, v = wl.make_host_tensors(w)
+    a = run_attn(w, q, k, v)
+    perm = np.random.default_rng(1).permutation(w.num_pool_blocks)
+    k2, v2 = np.empty_like(k), np.empty_like(v)
+    k2[perm], v2[perm] = k, v
+    w2 = wl.Workload("perm", 40, 8, w.context_lens,
+                     np.where(w.block_tables >= 0, perm[np.clip(w.block_tables, 0, None)],
+                              -1).astype(np.int32), w.num_pool_blocks, seed=w.seed)
+    b = run_attn(w2, q, k2, v2)
+    assert np.array_equal(a, b)
+
+
+def test_batch_independence_bitwise(device):
+    """Continuous batching: dropping or reordering requests leaves the others' rows alone."""
+    w = wl.custom([300, 1000, 77, 513, 16], 40, 8, seed=13)
+    q, k, v = wl.make_host_tensors(w)
+    a = run_attn(w, q, k, v).reshape(w.q_shape())
+    idx = [3, 0, 4]
+    sub = wl.subset(w, idx)
+    b = run_attn(sub, q[idx], k, v).reshape(sub.q_shape())
+    assert np.array_equal(b, a[idx])
+
+
+def test_gqa_equals_mha_with_repeated_kv(device):
+    w = wl.custom([300, 77, 600], 8, 2, seed=14)
+    q, k, v = wl.make_host_tensors(w)
+    a = run_attn(w, q, k, v)
+    w_mha = wl.Workload("mha", 8, 8, w.context_lens, w.block_tables, w.num_pool_blocks, seed=w.seed)
+    b = run_attn(w_mha, q, np.repeat(k, 4, axis=1), np.repeat(v, 4, axis=1))
+    ref = check(w, q, k, v, a, "gqa")
+    cb = oracle.compare(b, ref)
+    assert cb["rel_l2"] <= REL_L2 and cb["max_abs"] <= MAX_ABS
+
+
+def test_shared_prefix_blocks(device):
+    """Several requests may map the same physical blocks (read-only sharing)."""
+    w = wl.custom([200, 200, 90], 8, 2, seed=15, num_pool_blocks=64)
+    w.block_tables[1, :5] = w.block_tables[0, :5]
+    q, k, v = wl.make_host_tensors(w)
+    check(w, q, k, v, run_attn(w, q, k, v))
+
+
+def test_grow_by_one_token(device):
+    """A request's cache grows by one row per decode step (paper Section II-A)."""
+    final = np.array([50, 515], np.int32)
+    w = wl.custom(final, 8, 2, seed=16, num_pool_blocks=64, maxb=40)   # tables cover the final lengths
+    q, k, v = wl.make_host_tensors(w)
+    for back in (3, 2, 1, 0):
+        w.context_lens = final - back      # the slots ahead already hold N(0,1) rows
+        assert (w.used_blocks() <= (w.block_tables >= 0).sum(1)).all()
+        check(w, q, k, v, run_attn(w, q, k, v), f"lens={w.context_lens.tolist()}")
+
+
+def test_cfg2_full_parity(device):
+    w = wl.cfg2_qwen32b()
+    q_d, k_d, v_d = device_tensors(w)
+    out = run_attn_dev(w, q_d, k_d, v_d, to_dev(w.block_tables), to_dev(w.context_lens))
+    torch.cuda.synchronize()
+    check(w, to_bits(q_d), to_bits(k_d), to_bits(v_d), to_bits(out))
+
+
+def test_cfg3_full_parity(device):
+    w = wl.cfg3_long_cot()
+    q_d, k_d, v_d = device_tensors(w)
+    out = run_attn_dev(w, q_d, k_d, v_d, to_dev(w.block_tables), to_dev(w.context_lens))
+    torch.cuda.synchronize()
+    got = to_bits(out)
+    q, k, v = to_bits(q_d), to_bits(k_d), to_bits(v_d)
+    del k_d, v_d
+    check(w, q, k, v, got)
+
+
+def test_corrupt_table_entries_are_not_followed(device):
+    """Ids outside the pool are never dereferenced: the tokens of such a block
+    drop out of the softmax, the other requests' rows are untouched."""
+    w = wl.custom([300, 1000, 77, 40], 40, 8, seed=19, num_pool_blocks=200, partition_size=128)
+    q, k, v = wl.make_host_tensors(w)
+    good = run_attn(w, q, k, v).reshape(w.q_shape())
+    bad = wl.Workload("bad", 40, 8, w.context_lens, w.block_tables.copy(), w.num_pool_blocks,
+                      partition_size=128, seed=w.seed)
+    bad.block_tables[0, 3] = -7
+    bad.block_tables[1, 10] = w.num_pool_blocks
+    bad.block_tables[1, 11] = 2 ** 31 - 1
+    bad.block_tables[3, :3] = -1            # nothing of request 3 is mapped
+    dev = [to_dev(x) for x in (q, k, v, bad.block_tables, bad.context_lens)]
+    out = run_attn_dev(bad, *dev, check_tables=False)
+    torch.cuda.synchronize()
+    got = to_bits(out).reshape(w.q_shape())
+    assert np.array_equal(got[2], good[2])
+    assert not got[3].any()
+    # requests 0 and 1 equal the checker's result with the unmapped tokens removed
+    keep = wl.custom([300 - 16, 1000 - 32], 40, 8, seed=1, num_pool_blocks=200)
+    keep.block_tables[0, :18] = np.delete(w.block_tables[0, :19], 3)
+    keep.block_tables[1, :61] = np.delete(w.block_tables[1, :63], [10, 11])
+    ref = oracle.paged_decode_attn(q[:2], k, v, keep.block_tables, keep.context_lens, w.scale)
+    c = oracle.compare(got[:2], ref)
+    assert c["max_abs"] <= MAX_ABS and c["rel_l2"] <= REL_L2, c

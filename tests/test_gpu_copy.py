@@ -1,0 +1,111 @@
+"""GPU parity of kv_blocks_gather / kv_blocks_scatter: bit-exact against the
+checker's byte copies, and attention unchanged by a migration."""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+from paper_2602_11530_amd import binding as pkv
+from paper_2602_11530_amd import workloads as wl
+
+from gpu_util import run_attn, to_bits, to_dev
+
+pytestmark = pytest.mark.gpu
+
+
+def gather_gpu(pool_d, ids, block_bytes):
+    nb = pool_d.shape[0]
+    assert len(ids) == 0 or (0 <= min(ids) and max(ids) < nb)
+    ids_d = to_dev(np.asarray(ids, np.int32))
+    st = torch.full((len(ids) * block_bytes // 2,), 0x5A5A, dtype=torch.int16, device=pool_d.device)
+    pkv.kv_blocks_gather(pool_d, ids_d, st, len(ids), block_bytes, nb)
+    torch.cuda.synchronize()
+    return st
+
+
+@pytest.mark.parametrize("hkv,n", [(8, 37), (2, 5), (1, 1), (8, 1000)])
+def test_gather_scatter_bit_exact(device, hkv, n):
+    rng = np.random.default_rng(100 + n)
+    NB = max(2 * n, 8)
+    pool = rng.integers(0, 65536, size=(NB, hkv, 16, 128)).astype(np.uint16)
+    bb = hkv * 16 * 128 * 2
+    ids = rng.permutation(NB)[:n].astype(np.int32)
+    pool_d = to_dev(pool)
+    st = gather_gpu(pool_d, ids, bb)
+    want = oracle.kv_blocks_gather(pool, ids)
+    assert np.array_equal(to_bits(st).reshape(want.shape), want)
+    assert np.array_equal(to_bits(pool_d), pool), "gather must not write the pool"
+
+    new_ids = rng.permutation(NB)[:n].astype(np.int32)
+    pkv.kv_blocks_scatter(st, pool_d, to_dev(new_ids), n, bb, NB)
+    torch.cuda.synchronize()
+    want_pool = oracle.kv_blocks_scatter(want, pool, new_ids)
+    assert np.array_equal(to_bits(pool_d), want_pool)
+
+
+def test_odd_block_bytes_and_empty_list(device):
+    """block_bytes only has to be a multiple of 16; an empty list is a no-op."""
+    rng = np.random.default_rng(7)
+    for bb in (16, 48, 4096 + 16, 65536, 100000 - 100000 % 16):
+        NB = 9
+        pool = rng.integers(0, 65536, size=(NB, bb // 2)).astype(np.uint16)
+        ids = np.array([8, 0, 3], np.int32)
+        pool_d = to_dev(pool)
+        st = gather_gpu(pool_d, ids, bb)
+        assert np.array_equal(to_bits(st).reshape(3, -1), pool[ids])
+        dst = to_dev(np.zeros_like(pool))
+        pkv.kv_blocks_scatter(st, dst, to_dev(ids), 3, bb, NB)
+        torch.cuda.synchronize()
+        want = np.zeros_like(pool)
+        want[ids] = pool[ids]
+        assert np.array_equal(to_bits(dst), want)
+    pkv.kv_blocks_gather(pool_d, to_dev(ids), st, 0, bb, NB)
+    pkv.kv_blocks_scatter(st, pool_d, to_dev(ids), 0, bb, NB)
+    torch.cuda.synchronize()
+    assert np.array_equal(to_bits(pool_d), pool)
+
+
+def test_migration_keeps_attention_bitwise(device):
+    """Gather a quarter of the requests, scatter into reshuffled blocks, rewrite
+    their tables: every block image and the attention output are unchanged."""
+    w = wl.custom([300, 1000, 77, 513, 16, 2000, 40, 900], 40, 8, seed=21, num_pool_blocks=400)
+    q, k, v = wl.make_host_tensors(w)
+    before = run_attn(w, q, k, v)
+    mig = wl.make_migration(w, 0.25)
+    pools = []
+    for pool in (k, v):
+        pool_d = to_dev(pool)
+        st = gather_gpu(pool_d, mig.old_ids, w.block_bytes)
+        pkv.kv_blocks_scatter(st, pool_d, to_dev(mig.new_ids), len(mig.new_ids), w.block_bytes,
+                              w.num_pool_blocks)
+        torch.cuda.synchronize()
+        got = to_bits(pool_d).reshape(pool.shape)
+        want = oracle.kv_blocks_scatter(oracle.kv_blocks_gather(pool, mig.old_ids), pool, mig.new_ids)
+        assert np.array_equal(got, want)
+        assert np.array_equal(got[mig.new_ids], pool[mig.old_ids])
+        pools.append(got)
+    w2 = wl.Workload("after", 40, 8, w.context_lens, mig.tables_after, w.num_pool_blocks, seed=w.seed)
+    after = run_attn(w2, q, pools[0], pools[1])
+    assert np.array_equal(before, after)
+
+
+def test_out_of_range_ids_are_skipped(device):
+    """The device never follows an id outside the pool: those list entries are
+    skipped and everything else is copied as usual."""
+    rng = np.random.default_rng(9)
+    NB, bb = 12, 8 * 16 * 128 * 2
+    pool = rng.integers(0, 65536, size=(NB, bb // 2)).astype(np.uint16)
+    ids = np.array([3, -1, 11, NB, 0, 2 ** 31 - 1, -2 ** 31], np.int32)
+    ok = (ids >= 0) & (ids < NB)
+    pool_d = to_dev(pool)
+    st = torch.full((len(ids) * bb // 2,), 0x5A5A, dtype=torch.int16, device=pool_d.device)
+    pkv.kv_blocks_gather(pool_d, to_dev(ids), st, len(ids), bb, NB)
+    torch.cuda.synchronize()
+    got = to_bits(st).reshape(len(ids), -1)
+    assert np.array_equal(got[ok], pool[ids[ok]]) and (got[~ok] == 0x5A5A).all()
+    dst = to_dev(np.zeros_like(pool))
+    pkv.kv_blocks_scatter(st, dst, to_dev(ids), len(ids), bb, NB)
+    torch.cuda.synchronize()
+    want = np.zeros_like(pool)
+    want[ids[ok]] = pool[ids[ok]]
+    assert np.array_equal(to_bits(dst), want)
