@@ -1,17 +1,30 @@
-// Paged decode attention, partition pass, for gfx950 (wave64).
+// Paged decode attention, partition pass, for gfx950 (wave64, MFMA).
 //
 // One wavefront owns one (request, KV head, context partition) and streams that
 // partition's K and V rows exactly once; the G query heads of the GQA group
 // share every byte read (decode attends over the request's whole KV cache and
-// is bound by memory bandwidth, paper Section II-A).
+// is bound by memory bandwidth, paper Section II-A).  Both products run on the
+// matrix cores with the group padded to 16 rows, which leaves the vector ALU
+// with the softmax of 4 scores per lane per block and keeps the wave's time in
+// its loads.
 //
-// Lane map (natural pool layout, a K or V row is 128 bf16 = 16 lanes x 16 B):
-//   lane = 16*r + c;  c = 16-byte column chunk (dims 8c..8c+7),  r = token row.
-//   One 16-byte load per lane covers 4 consecutive tokens (1 KiB, contiguous);
-//   a 16-token block of one KV head is 4 such loads for K and 4 for V.
-// Scores: per-lane partial dot over 8 dims, then a 16-lane DPP all-reduce.
-// Each token row r keeps its own online-softmax state; the four states are
-// merged once at the end of the partition.
+// Per 16-token block, lane = 16*c + n:
+//   S^T = K . Q^T   four v_mfma_f32_16x16x32_bf16 (k = 32 dims each).
+//         A = K rows: lane (n, c) loads the 16 bytes at dims 32*jj + 8*c of
+//         token tau(n) = 4*(n%4) + n/4, straight from the pool (a 64-byte run
+//         per token per load).  B = q: lane (n, c) holds the same dims of head n.
+//         The result leaves lane (n, c) with head n's scores for tokens 4*i + c.
+//   P     = exp2(score - m) in fp32, split into bf16 hi + lo parts so that the
+//         weights keep ~16 mantissa bits through the second product.
+//   O    += P . V   eight v_mfma_f32_16x16x16_bf16 per part.  V is loaded in its
+//         natural order (lane (n, c) gets dims 8n..8n+7 of tokens 4*e + c, four
+//         fully contiguous 1 KiB loads); the operand for output dims 8*n + i
+//         pairs up the i-th halves of those four loads with v_perm_b32.  The
+//         token order 4*e + c is exactly the one the scores came out in, so P
+//         needs no shuffle between the two products.
+// The running maximum m is only raised when a score exceeds it by more than
+// 2^kLazyLog2; any reference value gives the same softmax, and the bound keeps
+// every weight within fp32/bf16 range.
 #include "pkv_kernels.h"
 
 namespace pkv {
@@ -19,33 +32,26 @@ namespace {
 
 constexpr int kWavesPerGroup = 4;
 constexpr float kNegInf = -__builtin_huge_valf();
+constexpr float kLazyLog2 = 8.f;
 
-__device__ __forceinline__ float bf16_lo(uint32_t w) { return __uint_as_float(w << 16); }
-__device__ __forceinline__ float bf16_hi(uint32_t w) { return __uint_as_float(w & 0xffff0000u); }
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
+typedef short s16x4 __attribute__((ext_vector_type(4)));
+typedef float f32x4 __attribute__((ext_vector_type(4)));
+typedef float f32x2 __attribute__((ext_vector_type(2)));
+typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
 
-// fp32 -> bf16, round to nearest even (finite inputs).
-__device__ __forceinline__ uint32_t f32_to_bf16_rne(float f) {
-  const uint32_t u = __float_as_uint(f);
-  return (u + 0x7fffu + ((u >> 16) & 1u)) >> 16;
+// Two fp32 -> packed bf16, round to nearest even (v_cvt_pk_bf16_f32).
+__device__ __forceinline__ uint32_t pack_bf16(float lo, float hi) {
+  const f32x2 f = {lo, hi};
+  return __builtin_bit_cast(uint32_t, __builtin_convertvector(f, bf16x2));
+}
+// The same rounding, then the fp32 value of what was kept.
+__device__ __forceinline__ float bf16_round(float x, uint32_t& bits) {
+  bits = pack_bf16(x, 0.f) & 0xffffu;
+  return __uint_as_float(bits << 16);
 }
 
-// Sum over the 16 lanes of a DPP row; every lane of the row gets the total.
-__device__ __forceinline__ float row16_allreduce_add(float x) {
-  x += __uint_as_float(__builtin_amdgcn_update_dpp(0u, __float_as_uint(x), 0xB1, 0xF, 0xF, true));   // quad_perm [1,0,3,2]
-  x += __uint_as_float(__builtin_amdgcn_update_dpp(0u, __float_as_uint(x), 0x4E, 0xF, 0xF, true));   // quad_perm [2,3,0,1]
-  x += __uint_as_float(__builtin_amdgcn_update_dpp(0u, __float_as_uint(x), 0x141, 0xF, 0xF, true));  // row_half_mirror
-  x += __uint_as_float(__builtin_amdgcn_update_dpp(0u, __float_as_uint(x), 0x140, 0xF, 0xF, true));  // row_mirror
-  return x;
-}
-
-__device__ __forceinline__ void unpack8(const u32x4& w, float (&f)[8]) {
-  f[0] = bf16_lo(w.x); f[1] = bf16_hi(w.x);
-  f[2] = bf16_lo(w.y); f[3] = bf16_hi(w.y);
-  f[4] = bf16_lo(w.z); f[5] = bf16_hi(w.z);
-  f[6] = bf16_lo(w.w); f[7] = bf16_hi(w.w);
-}
-
-template <int G>
 __global__ __launch_bounds__(kWavesPerGroup * 64) void attn_partition_kernel(AttnLaunch a) {
   __shared__ int s_blk[kMaxPartition / kBlockTokens];
 
@@ -56,15 +62,15 @@ __global__ __launch_bounds__(kWavesPerGroup * 64) void attn_partition_kernel(Att
   const int wave = threadIdx.x >> 6;
   const int lane = threadIdx.x & 63;
   const int kvh = blockIdx.y * kWavesPerGroup + wave;
-  const int r = lane >> 4, c = lane & 15;
+  const int n = lane & 15, c = lane >> 4;
+  const int G = a.G;
 
   if (t0 >= L) {
     // Nothing to attend.  An empty request still owes a zero row when this
     // pass writes the output itself.
-    if (L <= 0 && p == 0 && a.NP == 1 && kvh < a.Hkv && r == 0) {
-#pragma unroll
+    if (L <= 0 && p == 0 && a.NP == 1 && kvh < a.Hkv && c == 0) {
       for (int h = 0; h < G; ++h)
-        *(u32x4*)(a.out + ((int64_t)s * a.Hq + kvh * G + h) * kHeadDim + 8 * c) = u32x4{0, 0, 0, 0};
+        *(u32x4*)(a.out + ((int64_t)s * a.Hq + kvh * G + h) * kHeadDim + 8 * n) = u32x4{0, 0, 0, 0};
     }
     return;
   }
@@ -72,6 +78,7 @@ __global__ __launch_bounds__(kWavesPerGroup * 64) void attn_partition_kernel(Att
   const int nblk = (t1 - t0 + kBlockTokens - 1) / kBlockTokens;
 
   // Stage this partition's physical block ids in LDS (one coalesced read).
+  // Ids outside the pool become -1 and are never followed.
   for (int i = threadIdx.x; i < nblk; i += blockDim.x) {
     const int id = a.block_tables[(int64_t)s * a.MAXB + t0 / kBlockTokens + i];
     s_blk[i] = ((unsigned)id < (unsigned)a.NB) ? id : -1;
@@ -79,170 +86,165 @@ __global__ __launch_bounds__(kWavesPerGroup * 64) void attn_partition_kernel(Att
   __syncthreads();
   if (kvh >= a.Hkv) return;
 
-  // q for the group, fp32, pre-multiplied by scale*log2(e): softmax runs on exp2.
-  float qf[G][8];
+  // q as the B operand of the score product: lane (n, c) holds dims
+  // 32*jj + 8*c .. +7 of head n; heads beyond the group are zero rows.
+  u32x4 qop[4];
+  {
+    const int hq = kvh * G + min(n, G - 1);
+    const u32x4* qp = (const u32x4*)(a.q + ((int64_t)s * a.Hq + hq) * kHeadDim) + c;
 #pragma unroll
-  for (int h = 0; h < G; ++h) {
-    const u32x4 w = *(const u32x4*)(a.q + ((int64_t)s * a.Hq + kvh * G + h) * kHeadDim + 8 * c);
-    unpack8(w, qf[h]);
-#pragma unroll
-    for (int i = 0; i < 8; ++i) qf[h][i] *= a.scale_log2e;
-  }
-
-  float m[G], l[G], acc[G][8];
-#pragma unroll
-  for (int h = 0; h < G; ++h) {
-    m[h] = kNegInf;
-    l[h] = 0.f;
-#pragma unroll
-    for (int i = 0; i < 8; ++i) acc[h][i] = 0.f;
+    for (int jj = 0; jj < 4; ++jj) {
+      const u32x4 w = qp[4 * jj];
+      qop[jj] = (n < G) ? w : u32x4{0, 0, 0, 0};
+    }
   }
 
   const int64_t head_elems = (int64_t)kBlockTokens * kHeadDim;  // one (block, KV head) slab
   const int64_t block_elems = (int64_t)a.Hkv * head_elems;
-  // Ids outside the pool were replaced by -1 when staged; such a block is read
-  // from block 0 (always mapped) and masked out below.
-  auto slab = [&](const uint16_t* pool, int b) -> const u32x4* {
-    const int phys = max(__builtin_amdgcn_readfirstlane(s_blk[b]), 0);
-    return (const u32x4*)(pool + (int64_t)phys * block_elems + (int64_t)kvh * head_elems) + lane;
-  };
+  const int tau = 4 * (n & 3) + (n >> 2);
+  const int koff = tau * 16 + c;   // in 16-byte units within the slab
 
   u32x4 kq[4], vq[4];
+  int phys = __builtin_amdgcn_readfirstlane(s_blk[0]);
   {
-    const u32x4* kp = slab(a.k_pool, 0);
-    const u32x4* vp = slab(a.v_pool, 0);
+    const int64_t base = (int64_t)max(phys, 0) * block_elems + (int64_t)kvh * head_elems;
+    const u32x4* kp = (const u32x4*)(a.k_pool + base) + koff;
+    const u32x4* vp = (const u32x4*)(a.v_pool + base) + lane;
 #pragma unroll
-    for (int j = 0; j < 4; ++j) { kq[j] = kp[64 * j]; vq[j] = vp[64 * j]; }
+    for (int j = 0; j < 4; ++j) { kq[j] = kp[4 * j]; vq[j] = vp[64 * j]; }
   }
+
+  float m = kNegInf;   // running reference maximum of head n (log2 units), same in all four c groups
+  float l = 0.f;       // this lane's share of the softmax denominator
+  f32x4 o[8];          // o[i][r]: head 4*c + r, dim 8*n + i
+#pragma unroll
+  for (int i = 0; i < 8; ++i) o[i] = f32x4{0.f, 0.f, 0.f, 0.f};
 
   for (int b = 0; b < nblk; ++b) {
     // Prefetch the next block's slabs while this one is consumed.
     u32x4 kn[4], vn[4];
 #pragma unroll
     for (int j = 0; j < 4; ++j) { kn[j] = kq[j]; vn[j] = vq[j]; }
+    int phys_next = phys;
     if (b + 1 < nblk) {
-      const u32x4* kp = slab(a.k_pool, b + 1);
-      const u32x4* vp = slab(a.v_pool, b + 1);
+      phys_next = __builtin_amdgcn_readfirstlane(s_blk[b + 1]);
+      const int64_t base = (int64_t)max(phys_next, 0) * block_elems + (int64_t)kvh * head_elems;
+      const u32x4* kp = (const u32x4*)(a.k_pool + base) + koff;
+      const u32x4* vp = (const u32x4*)(a.v_pool + base) + lane;
 #pragma unroll
-      for (int j = 0; j < 4; ++j) { kn[j] = kp[64 * j]; vn[j] = vp[64 * j]; }
+      for (int j = 0; j < 4; ++j) { kn[j] = kp[4 * j]; vn[j] = vp[64 * j]; }
     }
 
-    const int tb = t0 + b * kBlockTokens + r;   // this lane's token for j = 0
-    const bool mapped = s_blk[b] >= 0;
-    float sc[4][G];
+    if (phys >= 0) {
+      f32x4 sc = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
-    for (int j = 0; j < 4; ++j) {
-      float kf[8];
-      unpack8(kq[j], kf);
-      const bool valid = (tb + 4 * j < t1) && mapped;
+      for (int jj = 0; jj < 4; ++jj)
+        sc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, kq[jj]),
+                                                     __builtin_bit_cast(bf16x8, qop[jj]), sc, 0, 0, 0);
+      float x[4] = {sc.x * a.scale_log2e, sc.y * a.scale_log2e, sc.z * a.scale_log2e,
+                    sc.w * a.scale_log2e};
+      const int tb = t0 + b * kBlockTokens + c;   // token of element 0; element e is tb + 4e
+      if (b + 1 == nblk) {
+        // Last block: masked slots may hold anything (NaN included), so both the
+        // scores and the V rows are replaced by select, never scaled by zero.
 #pragma unroll
-      for (int h = 0; h < G; ++h) {
-        float d = 0.f;
-#pragma unroll
-        for (int i = 0; i < 8; ++i) d = __builtin_fmaf(qf[h][i], kf[i], d);
-        d = row16_allreduce_add(d);
-        sc[j][h] = valid ? d : kNegInf;   // select, never multiply: the slot may hold NaN
+        for (int e = 0; e < 4; ++e) {
+          const bool valid = tb + 4 * e < t1;
+          x[e] = valid ? x[e] : kNegInf;
+          if (!valid) vq[e] = u32x4{0, 0, 0, 0};
+        }
       }
-      if (!valid) vq[j] = u32x4{0, 0, 0, 0};
-    }
+      const float mx = fmaxf(fmaxf(x[0], x[1]), fmaxf(x[2], x[3]));
+      if (__any(mx > m + kLazyLog2)) {
+        float mg = fmaxf(mx, __shfl_xor(mx, 16));
+        mg = fmaxf(mg, __shfl_xor(mg, 32));
+        const float mnew = fmaxf(m, mg);          // finite: a mapped block has a valid token
+        const float alpha = __builtin_amdgcn_exp2f(m - mnew);
+        l *= alpha;
+        float ar[4];
+#pragma unroll
+        for (int r = 0; r < 4; ++r) ar[r] = __shfl(alpha, 4 * c + r);
+#pragma unroll
+        for (int i = 0; i < 8; ++i) {
+          o[i].x *= ar[0]; o[i].y *= ar[1]; o[i].z *= ar[2]; o[i].w *= ar[3];
+        }
+        m = mnew;
+      }
+      float pw[4];
+#pragma unroll
+      for (int e = 0; e < 4; ++e) pw[e] = __builtin_amdgcn_exp2f(x[e] - m);
+      l += (pw[0] + pw[1]) + (pw[2] + pw[3]);
 
-    float pw[4][G];
+      // P = hi + lo in bf16.
+      uint32_t hb[4];
+      float lo[4];
 #pragma unroll
-    for (int h = 0; h < G; ++h) {
-      const float mb = fmaxf(fmaxf(sc[0][h], sc[1][h]), fmaxf(sc[2][h], sc[3][h]));
-      const float mn = fmaxf(m[h], mb);
-      const float ms = (mn == kNegInf) ? 0.f : mn;   // row without a valid token yet
-      const float alpha = __builtin_amdgcn_exp2f(m[h] - ms);
-      float ps = 0.f;
+      for (int e = 0; e < 4; ++e) lo[e] = pw[e] - bf16_round(pw[e], hb[e]);
+      const u32x2 phi = {hb[0] | (hb[1] << 16), hb[2] | (hb[3] << 16)};
+      const u32x2 plo = {pack_bf16(lo[0], lo[1]), pack_bf16(lo[2], lo[3])};
+      const s16x4 pa = __builtin_bit_cast(s16x4, phi);
+      const s16x4 pb = __builtin_bit_cast(s16x4, plo);
+
 #pragma unroll
-      for (int j = 0; j < 4; ++j) {
-        pw[j][h] = __builtin_amdgcn_exp2f(sc[j][h] - ms);
-        ps += pw[j][h];
+      for (int i = 0; i < 8; ++i) {
+        const int wsel = i >> 1;
+        const uint32_t sel = (i & 1) ? 0x07060302u : 0x05040100u;
+        const u32x2 vb = {__builtin_amdgcn_perm(vq[1][wsel], vq[0][wsel], sel),
+                          __builtin_amdgcn_perm(vq[3][wsel], vq[2][wsel], sel)};
+        const s16x4 vop = __builtin_bit_cast(s16x4, vb);
+        o[i] = __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(pa, vop, o[i], 0, 0, 0);
+        o[i] = __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(pb, vop, o[i], 0, 0, 0);
       }
-      l[h] = l[h] * alpha + ps;
-#pragma unroll
-      for (int i = 0; i < 8; ++i) acc[h][i] *= alpha;
-      m[h] = mn;
-    }
-#pragma unroll
-    for (int j = 0; j < 4; ++j) {
-      float vf[8];
-      unpack8(vq[j], vf);
-#pragma unroll
-      for (int h = 0; h < G; ++h)
-#pragma unroll
-        for (int i = 0; i < 8; ++i) acc[h][i] = __builtin_fmaf(pw[j][h], vf[i], acc[h][i]);
     }
 
 #pragma unroll
     for (int j = 0; j < 4; ++j) { kq[j] = kn[j]; vq[j] = vn[j]; }
+    phys = phys_next;
   }
 
-  // Merge the four token-row states (lanes c, c+16, c+32, c+48).
-#pragma unroll
-  for (int h = 0; h < G; ++h) {
-    float ma = fmaxf(m[h], __shfl_xor(m[h], 16));
-    ma = fmaxf(ma, __shfl_xor(ma, 32));
-    const float f = (m[h] == kNegInf) ? 0.f : __builtin_amdgcn_exp2f(m[h] - ma);
-    float lr = l[h] * f;
-    lr += __shfl_xor(lr, 16);
-    lr += __shfl_xor(lr, 32);
-#pragma unroll
-    for (int i = 0; i < 8; ++i) {
-      float x = acc[h][i] * f;
-      x += __shfl_xor(x, 16);
-      x += __shfl_xor(x, 32);
-      acc[h][i] = x;
-    }
-    m[h] = ma;
-    l[h] = lr;
-  }
+  // Denominator of head n: sum the four c groups.
+  l += __shfl_xor(l, 16);
+  l += __shfl_xor(l, 32);
 
-  if (r != 0) return;
   if (a.NP == 1) {
 #pragma unroll
-    for (int h = 0; h < G; ++h) {
-      const float inv = l[h] > 0.f ? 1.f / l[h] : 0.f;   // no mapped token at all: zero row
-      u32x4 w;
-      w.x = f32_to_bf16_rne(acc[h][0] * inv) | (f32_to_bf16_rne(acc[h][1] * inv) << 16);
-      w.y = f32_to_bf16_rne(acc[h][2] * inv) | (f32_to_bf16_rne(acc[h][3] * inv) << 16);
-      w.z = f32_to_bf16_rne(acc[h][4] * inv) | (f32_to_bf16_rne(acc[h][5] * inv) << 16);
-      w.w = f32_to_bf16_rne(acc[h][6] * inv) | (f32_to_bf16_rne(acc[h][7] * inv) << 16);
-      *(u32x4*)(a.out + ((int64_t)s * a.Hq + kvh * G + h) * kHeadDim + 8 * c) = w;
+    for (int r = 0; r < 4; ++r) {
+      const int h = 4 * c + r;
+      const float lh = __shfl(l, h);
+      if (h < G) {
+        const float inv = lh > 0.f ? 1.f / lh : 0.f;   // no mapped token at all: zero row
+        u32x4 w;
+        w.x = pack_bf16(o[0][r] * inv, o[1][r] * inv);
+        w.y = pack_bf16(o[2][r] * inv, o[3][r] * inv);
+        w.z = pack_bf16(o[4][r] * inv, o[5][r] * inv);
+        w.w = pack_bf16(o[6][r] * inv, o[7][r] * inv);
+        *(u32x4*)(a.out + ((int64_t)s * a.Hq + kvh * G + h) * kHeadDim + 8 * n) = w;
+      }
     }
   } else {
 #pragma unroll
-    for (int h = 0; h < G; ++h) {
-      const int64_t row = ((int64_t)s * a.NP + p) * a.Hq + kvh * G + h;
-      float4* dst = (float4*)(a.ws_acc + row * kHeadDim + 8 * c);
-      dst[0] = make_float4(acc[h][0], acc[h][1], acc[h][2], acc[h][3]);
-      dst[1] = make_float4(acc[h][4], acc[h][5], acc[h][6], acc[h][7]);
-      if (c == 0) a.ws_ml[row] = make_float2(m[h], l[h]);
+    for (int r = 0; r < 4; ++r) {
+      const int h = 4 * c + r;
+      if (h < G) {
+        const int64_t row = ((int64_t)s * a.NP + p) * a.Hq + kvh * G + h;
+        float4* dst = (float4*)(a.ws_acc + row * kHeadDim + 8 * n);
+        dst[0] = make_float4(o[0][r], o[1][r], o[2][r], o[3][r]);
+        dst[1] = make_float4(o[4][r], o[5][r], o[6][r], o[7][r]);
+      }
+    }
+    if (c == 0 && n < G) {
+      const int64_t row = ((int64_t)s * a.NP + p) * a.Hq + kvh * G + n;
+      a.ws_ml[row] = make_float2(m, l);
     }
   }
-}
-
-template <int G>
-hipError_t launch_g(const AttnLaunch& a, hipStream_t stream) {
-  dim3 grid((unsigned)(a.S * a.NP), (unsigned)((a.Hkv + kWavesPerGroup - 1) / kWavesPerGroup), 1);
-  hipLaunchKernelGGL(attn_partition_kernel<G>, grid, dim3(kWavesPerGroup * 64), 0, stream, a);
-  return hipGetLastError();
 }
 
 }  // namespace
 
 hipError_t launch_attn_partition(const AttnLaunch& a, hipStream_t stream) {
-  switch (a.G) {
-    case 1: return launch_g<1>(a, stream);
-    case 2: return launch_g<2>(a, stream);
-    case 3: return launch_g<3>(a, stream);
-    case 4: return launch_g<4>(a, stream);
-    case 5: return launch_g<5>(a, stream);
-    case 6: return launch_g<6>(a, stream);
-    case 7: return launch_g<7>(a, stream);
-    case 8: return launch_g<8>(a, stream);
-    default: return hipErrorInvalidValue;
-  }
+  dim3 grid((unsigned)(a.S * a.NP), (unsigned)((a.Hkv + kWavesPerGroup - 1) / kWavesPerGroup), 1);
+  hipLaunchKernelGGL(attn_partition_kernel, grid, dim3(kWavesPerGroup * 64), 0, stream, a);
+  return hipGetLastError();
 }
 
 }  // namespace pkv

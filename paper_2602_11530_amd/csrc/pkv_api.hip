@@ -26,7 +26,7 @@ int check_shape(const pkv_attn_shape* sh, Geometry* g) {
   if (sh->head_dim != pkv::kHeadDim || sh->block_size != pkv::kBlockTokens) return PKV_ERR_SHAPE;
   if (sh->num_q_heads % sh->num_kv_heads != 0) return PKV_ERR_SHAPE;
   const int G = sh->num_q_heads / sh->num_kv_heads;
-  if (G > 8) return PKV_ERR_SHAPE;
+  if (G > pkv::kMaxGroup) return PKV_ERR_SHAPE;
   if (sh->max_blocks_per_seq <= 0) return PKV_ERR_SHAPE;
   if ((int64_t)sh->max_blocks_per_seq * pkv::kBlockTokens > INT32_MAX) return PKV_ERR_SHAPE;
   const int cap = sh->max_blocks_per_seq * pkv::kBlockTokens;

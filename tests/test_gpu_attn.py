@@ -35,7 +35,8 @@ def test_cfg1_tiny(device, poison):
 EDGE = [1, 15, 16, 17, 31, 32, 33, 0, 255, 256, 257, 511, 512, 513, 2, 1000]
 
 
-@pytest.mark.parametrize("hq,hkv", [(8, 2), (40, 8), (5, 1), (8, 8), (6, 2), (16, 2)])
+@pytest.mark.parametrize("hq,hkv", [(8, 2), (40, 8), (5, 1), (8, 8), (6, 2), (16, 2), (16, 1), (12, 1),
+                                    (9, 3)])
 @pytest.mark.parametrize("P", [0, 16, 512])
 def test_edge_lengths(device, hq, hkv, P):
     w = wl.custom(EDGE, hq, hkv, seed=31 + hq, num_pool_blocks=400, partition_size=P)
