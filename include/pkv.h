@@ -45,7 +45,7 @@ typedef struct {
   int32_t block_size;         /* B: 16 tokens per physical block                         */
   int32_t max_blocks_per_seq; /* MAXB: row stride of block_tables, >= ceil(L_s/B)        */
   int32_t partition_size;     /* split-K partition in tokens: a multiple of B in
-                                 [B, 4096], or 0 to let the library choose               */
+                                 [B, 1024], or 0 to let the library choose               */
   int32_t max_context_len;    /* host upper bound on every context_lens[s]; 0 means
                                  MAXB*B.  A smaller bound only shrinks the launch;
                                  a request longer than the bound is attended up to it.   */

@@ -16,6 +16,9 @@ FLAGS = [
     "-fno-gpu-rdc",
     # packed fp32 arithmetic is kept off for every kernel of this library
     "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
+    # keep MFMA accumulators in VGPRs: the softmax rescale touches them with
+    # vector ops, and AGPR placement costs a copy each way per block
+    "-mllvm", "-amdgpu-mfma-vgpr-form",
     "-Wall", "-Wno-unused-command-line-argument", "-Wno-unknown-warning-option",
 ]
 

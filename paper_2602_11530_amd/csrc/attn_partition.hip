@@ -30,9 +30,19 @@
 namespace pkv {
 namespace {
 
-constexpr int kWavesPerGroup = 4;
+#ifndef PKV_WAVES_PER_GROUP
+#define PKV_WAVES_PER_GROUP 4
+#endif
+#ifndef PKV_MIN_WAVES_PER_EU
+#define PKV_MIN_WAVES_PER_EU 1
+#endif
+constexpr int kWavesPerGroup = PKV_WAVES_PER_GROUP;
 constexpr float kNegInf = -__builtin_huge_valf();
 constexpr float kLazyLog2 = 8.f;
+#ifndef PKV_RING
+#define PKV_RING 4
+#endif
+constexpr int kRing = PKV_RING;   // 16-token blocks in flight per wavefront (register ring)
 
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
@@ -52,9 +62,8 @@ __device__ __forceinline__ float bf16_round(float x, uint32_t& bits) {
   return __uint_as_float(bits << 16);
 }
 
-__global__ __launch_bounds__(kWavesPerGroup * 64) void attn_partition_kernel(AttnLaunch a) {
-  __shared__ int s_blk[kMaxPartition / kBlockTokens];
-
+__global__ __launch_bounds__(kWavesPerGroup * 64)
+__attribute__((amdgpu_waves_per_eu(PKV_MIN_WAVES_PER_EU))) void attn_partition_kernel(AttnLaunch a) {
   const int s = blockIdx.x / a.NP;
   const int p = blockIdx.x - s * a.NP;
   const int L = min(max(a.context_lens[s], 0), a.max_ctx);
@@ -77,13 +86,15 @@ __global__ __launch_bounds__(kWavesPerGroup * 64) void attn_partition_kernel(Att
   const int t1 = min(L, t0 + a.P);
   const int nblk = (t1 - t0 + kBlockTokens - 1) / kBlockTokens;
 
-  // Stage this partition's physical block ids in LDS (one coalesced read).
+  // This partition's physical block ids: lane i keeps entry i (a partition is at
+  // most 64 blocks), read with one coalesced load; v_readlane hands block b's id
+  // to the scalar unit with no memory access on the loads' address path.
   // Ids outside the pool become -1 and are never followed.
-  for (int i = threadIdx.x; i < nblk; i += blockDim.x) {
-    const int id = a.block_tables[(int64_t)s * a.MAXB + t0 / kBlockTokens + i];
-    s_blk[i] = ((unsigned)id < (unsigned)a.NB) ? id : -1;
+  int tbl = -1;
+  if (lane < nblk) {
+    const int id = a.block_tables[(int64_t)s * a.MAXB + t0 / kBlockTokens + lane];
+    tbl = ((unsigned)id < (unsigned)a.NB) ? id : -1;
   }
-  __syncthreads();
   if (kvh >= a.Hkv) return;
 
   // q as the B operand of the score product: lane (n, c) holds dims
@@ -104,102 +115,111 @@ __global__ __launch_bounds__(kWavesPerGroup * 64) void attn_partition_kernel(Att
   const int tau = 4 * (n & 3) + (n >> 2);
   const int koff = tau * 16 + c;   // in 16-byte units within the slab
 
-  u32x4 kq[4], vq[4];
-  int phys = __builtin_amdgcn_readfirstlane(s_blk[0]);
-  {
-    const int64_t base = (int64_t)max(phys, 0) * block_elems + (int64_t)kvh * head_elems;
-    const u32x4* kp = (const u32x4*)(a.k_pool + base) + koff;
-    const u32x4* vp = (const u32x4*)(a.v_pool + base) + lane;
-#pragma unroll
-    for (int j = 0; j < 4; ++j) { kq[j] = kp[4 * j]; vq[j] = vp[64 * j]; }
-  }
-
   float m = kNegInf;   // running reference maximum of head n (log2 units), same in all four c groups
   float l = 0.f;       // this lane's share of the softmax denominator
   f32x4 o[8];          // o[i][r]: head 4*c + r, dim 8*n + i
 #pragma unroll
   for (int i = 0; i < 8; ++i) o[i] = f32x4{0.f, 0.f, 0.f, 0.f};
 
-  for (int b = 0; b < nblk; ++b) {
-    // Prefetch the next block's slabs while this one is consumed.
-    u32x4 kn[4], vn[4];
+  // Issue the eight 16-byte loads of block b (K in operand order, V natural) and
+  // return its staged physical id.  The loads are issued unconditionally so that
+  // every wait in the loop knows exactly how many are outstanding: an unmapped
+  // block (-1) or one past the partition's end reads block 0 of KV head 0, which
+  // always exists, and is masked out or skipped when its turn comes.
+  auto issue = [&](u32x4 (&k)[4], u32x4 (&v)[4], int b) -> int {
+    const bool live = b < nblk;
+    const int phys = live ? __builtin_amdgcn_readlane(tbl, min(b, 63)) : -1;
+    const int64_t base = (phys >= 0) ? (int64_t)phys * block_elems + (int64_t)kvh * head_elems : 0;
+    const u32x4* kp = (const u32x4*)(a.k_pool + base) + koff;
+    const u32x4* vp = (const u32x4*)(a.v_pool + base) + lane;
 #pragma unroll
-    for (int j = 0; j < 4; ++j) { kn[j] = kq[j]; vn[j] = vq[j]; }
-    int phys_next = phys;
-    if (b + 1 < nblk) {
-      phys_next = __builtin_amdgcn_readfirstlane(s_blk[b + 1]);
-      const int64_t base = (int64_t)max(phys_next, 0) * block_elems + (int64_t)kvh * head_elems;
-      const u32x4* kp = (const u32x4*)(a.k_pool + base) + koff;
-      const u32x4* vp = (const u32x4*)(a.v_pool + base) + lane;
+    for (int j = 0; j < 4; ++j) k[j] = kp[4 * j];
 #pragma unroll
-      for (int j = 0; j < 4; ++j) { kn[j] = kp[4 * j]; vn[j] = vp[64 * j]; }
-    }
+    for (int j = 0; j < 4; ++j) v[j] = vp[64 * j];
+    return phys;
+  };
 
-    if (phys >= 0) {
-      f32x4 sc = {0.f, 0.f, 0.f, 0.f};
+  auto consume = [&](u32x4 (&k)[4], u32x4 (&v)[4], int b, int phys) {
+    f32x4 sc = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
-      for (int jj = 0; jj < 4; ++jj)
-        sc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, kq[jj]),
-                                                     __builtin_bit_cast(bf16x8, qop[jj]), sc, 0, 0, 0);
-      float x[4] = {sc.x * a.scale_log2e, sc.y * a.scale_log2e, sc.z * a.scale_log2e,
-                    sc.w * a.scale_log2e};
+    for (int jj = 0; jj < 4; ++jj)
+      sc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, k[jj]),
+                                                   __builtin_bit_cast(bf16x8, qop[jj]), sc, 0, 0, 0);
+    float x[4] = {sc.x * a.scale_log2e, sc.y * a.scale_log2e, sc.z * a.scale_log2e,
+                  sc.w * a.scale_log2e};
+    const bool edge = (b + 1 == nblk) || (phys < 0);
+    bool valid[4] = {true, true, true, true};
+    if (edge) {
+      // Last or unmapped block: masked slots may hold anything (NaN included), so
+      // scores, weights and V rows are replaced by select, never scaled by zero.
       const int tb = t0 + b * kBlockTokens + c;   // token of element 0; element e is tb + 4e
-      if (b + 1 == nblk) {
-        // Last block: masked slots may hold anything (NaN included), so both the
-        // scores and the V rows are replaced by select, never scaled by zero.
 #pragma unroll
-        for (int e = 0; e < 4; ++e) {
-          const bool valid = tb + 4 * e < t1;
-          x[e] = valid ? x[e] : kNegInf;
-          if (!valid) vq[e] = u32x4{0, 0, 0, 0};
-        }
+      for (int e = 0; e < 4; ++e) {
+        valid[e] = (tb + 4 * e < t1) && (phys >= 0);
+        x[e] = valid[e] ? x[e] : kNegInf;
+        if (!valid[e]) v[e] = u32x4{0, 0, 0, 0};
       }
-      const float mx = fmaxf(fmaxf(x[0], x[1]), fmaxf(x[2], x[3]));
-      if (__any(mx > m + kLazyLog2)) {
-        float mg = fmaxf(mx, __shfl_xor(mx, 16));
-        mg = fmaxf(mg, __shfl_xor(mg, 32));
-        const float mnew = fmaxf(m, mg);          // finite: a mapped block has a valid token
-        const float alpha = __builtin_amdgcn_exp2f(m - mnew);
-        l *= alpha;
-        float ar[4];
+    }
+    const float mx = fmaxf(fmaxf(x[0], x[1]), fmaxf(x[2], x[3]));
+    if (__any(mx > m + kLazyLog2)) {
+      float mg = fmaxf(mx, __shfl_xor(mx, 16));
+      mg = fmaxf(mg, __shfl_xor(mg, 32));
+      const float mnew = fmaxf(m, mg);   // finite: some lane of the head saw a valid token
+      const float alpha = __builtin_amdgcn_exp2f(m - mnew);
+      l *= alpha;
+      float ar[4];
 #pragma unroll
-        for (int r = 0; r < 4; ++r) ar[r] = __shfl(alpha, 4 * c + r);
-#pragma unroll
-        for (int i = 0; i < 8; ++i) {
-          o[i].x *= ar[0]; o[i].y *= ar[1]; o[i].z *= ar[2]; o[i].w *= ar[3];
-        }
-        m = mnew;
-      }
-      float pw[4];
-#pragma unroll
-      for (int e = 0; e < 4; ++e) pw[e] = __builtin_amdgcn_exp2f(x[e] - m);
-      l += (pw[0] + pw[1]) + (pw[2] + pw[3]);
-
-      // P = hi + lo in bf16.
-      uint32_t hb[4];
-      float lo[4];
-#pragma unroll
-      for (int e = 0; e < 4; ++e) lo[e] = pw[e] - bf16_round(pw[e], hb[e]);
-      const u32x2 phi = {hb[0] | (hb[1] << 16), hb[2] | (hb[3] << 16)};
-      const u32x2 plo = {pack_bf16(lo[0], lo[1]), pack_bf16(lo[2], lo[3])};
-      const s16x4 pa = __builtin_bit_cast(s16x4, phi);
-      const s16x4 pb = __builtin_bit_cast(s16x4, plo);
-
+      for (int r = 0; r < 4; ++r) ar[r] = __shfl(alpha, 4 * c + r);
 #pragma unroll
       for (int i = 0; i < 8; ++i) {
-        const int wsel = i >> 1;
-        const uint32_t sel = (i & 1) ? 0x07060302u : 0x05040100u;
-        const u32x2 vb = {__builtin_amdgcn_perm(vq[1][wsel], vq[0][wsel], sel),
-                          __builtin_amdgcn_perm(vq[3][wsel], vq[2][wsel], sel)};
-        const s16x4 vop = __builtin_bit_cast(s16x4, vb);
-        o[i] = __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(pa, vop, o[i], 0, 0, 0);
-        o[i] = __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(pb, vop, o[i], 0, 0, 0);
+        o[i].x *= ar[0]; o[i].y *= ar[1]; o[i].z *= ar[2]; o[i].w *= ar[3];
       }
+      m = mnew;
     }
-
+    float pw[4];
 #pragma unroll
-    for (int j = 0; j < 4; ++j) { kq[j] = kn[j]; vq[j] = vn[j]; }
-    phys = phys_next;
+    for (int e = 0; e < 4; ++e) pw[e] = __builtin_amdgcn_exp2f(x[e] - m);
+    if (edge) {
+#pragma unroll
+      for (int e = 0; e < 4; ++e) pw[e] = valid[e] ? pw[e] : 0.f;   // m may still be -inf here
+    }
+    l += (pw[0] + pw[1]) + (pw[2] + pw[3]);
+
+    // P = hi + lo in bf16.
+    uint32_t hb[4];
+    float lo[4];
+#pragma unroll
+    for (int e = 0; e < 4; ++e) lo[e] = pw[e] - bf16_round(pw[e], hb[e]);
+    const u32x2 phi = {hb[0] | (hb[1] << 16), hb[2] | (hb[3] << 16)};
+    const u32x2 plo = {pack_bf16(lo[0], lo[1]), pack_bf16(lo[2], lo[3])};
+    const s16x4 pa = __builtin_bit_cast(s16x4, phi);
+    const s16x4 pb = __builtin_bit_cast(s16x4, plo);
+#pragma unroll
+    for (int i = 0; i < 8; ++i) {
+      const int wsel = i >> 1;
+      const uint32_t sel = (i & 1) ? 0x07060302u : 0x05040100u;
+      const u32x2 vb = {__builtin_amdgcn_perm(v[1][wsel], v[0][wsel], sel),
+                        __builtin_amdgcn_perm(v[3][wsel], v[2][wsel], sel)};
+      const s16x4 vop = __builtin_bit_cast(s16x4, vb);
+      o[i] = __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(pa, vop, o[i], 0, 0, 0);
+      o[i] = __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(pb, vop, o[i], 0, 0, 0);
+    }
+  };
+
+  // A ring of kRing register buffers: kRing - 1 blocks are always in flight
+  // while one is consumed, and no buffer is ever copied.
+  u32x4 kbuf[kRing][4], vbuf[kRing][4];
+  int phys[kRing];
+#pragma unroll
+  for (int i = 0; i < kRing - 1; ++i) phys[i] = issue(kbuf[i], vbuf[i], i);
+  for (int b = 0; b < nblk; b += kRing) {
+#pragma unroll
+    for (int i = 0; i < kRing; ++i) {
+      constexpr int kAhead = kRing - 1;
+      const int slot = (i + kAhead) % kRing;
+      phys[slot] = issue(kbuf[slot], vbuf[slot], b + i + kAhead);
+      if (b + i < nblk) consume(kbuf[i], vbuf[i], b + i, phys[i]);
+    }
   }
 
   // Denominator of head n: sum the four c groups.

@@ -1,17 +1,30 @@
 // Split-K merge for paged decode attention on gfx950: combines the per-partition
 // (running max, partial sum, un-normalised output) triples of one (request,
 // query head) into the final bf16 row.  The maxima are in log2 units, as the
-// partition pass leaves them.
+// partition pass leaves them.  One wavefront per row; the lanes fetch the
+// partitions' statistics side by side, then stream the partial rows eight at a
+// time so that the pass is not a chain of dependent loads.
 #include "pkv_kernels.h"
 
 namespace pkv {
 namespace {
 
-constexpr int kRowsPerGroup = 4;   // one wavefront per (request, query head)
+constexpr int kRowsPerGroup = 4;   // wavefronts per workgroup
+constexpr int kBatch = 8;          // partial rows in flight per wavefront
+constexpr float kNegInf = -__builtin_huge_valf();
 
-__device__ __forceinline__ uint32_t f32_to_bf16_rne(float f) {
-  const uint32_t u = __float_as_uint(f);
-  return (u + 0x7fffu + ((u >> 16) & 1u)) >> 16;
+typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
+typedef float f32x2 __attribute__((ext_vector_type(2)));
+
+__device__ __forceinline__ float wave_max(float x) {
+#pragma unroll
+  for (int o = 32; o > 0; o >>= 1) x = fmaxf(x, __shfl_xor(x, o));
+  return x;
+}
+__device__ __forceinline__ float wave_sum(float x) {
+#pragma unroll
+  for (int o = 32; o > 0; o >>= 1) x += __shfl_xor(x, o);
+  return x;
 }
 
 __global__ __launch_bounds__(kRowsPerGroup * 64) void attn_reduce_kernel(AttnLaunch a) {
@@ -25,20 +38,44 @@ __global__ __launch_bounds__(kRowsPerGroup * 64) void attn_reduce_kernel(AttnLau
   if (np <= 0) { *dst = 0u; return; }
 
   const int64_t base = ((int64_t)s * a.NP) * a.Hq + h;   // + p*Hq per partition
-  float M = -__builtin_huge_valf();
-  for (int p = 0; p < np; ++p) M = fmaxf(M, a.ws_ml[base + (int64_t)p * a.Hq].x);
-  float lsum = 0.f, o0 = 0.f, o1 = 0.f;
-  for (int p = 0; p < np; ++p) {
-    const float2 ml = a.ws_ml[base + (int64_t)p * a.Hq];
-    // A partition whose blocks were all unmapped carries max = -inf, sum = 0.
-    const float w = (ml.x == -__builtin_huge_valf()) ? 0.f : __builtin_amdgcn_exp2f(ml.x - M);
-    const float2 v = *((const float2*)(a.ws_acc + (base + (int64_t)p * a.Hq) * kHeadDim) + lane);
-    lsum = __builtin_fmaf(w, ml.y, lsum);
-    o0 = __builtin_fmaf(w, v.x, o0);
-    o1 = __builtin_fmaf(w, v.y, o1);
+  float M = kNegInf;
+  for (int p0 = 0; p0 < np; p0 += 64) {
+    const int p = p0 + lane;
+    if (p < np) M = fmaxf(M, a.ws_ml[base + (int64_t)p * a.Hq].x);
   }
+  M = wave_max(M);
+
+  float lsum = 0.f, o0 = 0.f, o1 = 0.f;
+  for (int p0 = 0; p0 < np; p0 += 64) {
+    const int p = p0 + lane;
+    float w = 0.f;
+    if (p < np) {
+      const float2 ml = a.ws_ml[base + (int64_t)p * a.Hq];
+      // A partition whose blocks were all unmapped carries max = -inf, sum = 0.
+      w = (ml.x == kNegInf) ? 0.f : __builtin_amdgcn_exp2f(ml.x - M);
+      lsum = __builtin_fmaf(w, ml.y, lsum);
+    }
+    const int cnt = min(64, np - p0);
+    for (int j0 = 0; j0 < cnt; j0 += kBatch) {
+      float2 v[kBatch];
+      float wj[kBatch];
+#pragma unroll
+      for (int u = 0; u < kBatch; ++u) {
+        const int j = min(j0 + u, cnt - 1);   // clamped rows get weight 0
+        wj[u] = (j0 + u < cnt) ? __int_as_float(__builtin_amdgcn_readlane(__float_as_int(w), j)) : 0.f;
+        v[u] = *((const float2*)(a.ws_acc + (base + (int64_t)(p0 + j) * a.Hq) * kHeadDim) + lane);
+      }
+#pragma unroll
+      for (int u = 0; u < kBatch; ++u) {
+        o0 = __builtin_fmaf(wj[u], v[u].x, o0);
+        o1 = __builtin_fmaf(wj[u], v[u].y, o1);
+      }
+    }
+  }
+  lsum = wave_sum(lsum);
   const float inv = lsum > 0.f ? 1.f / lsum : 0.f;
-  *dst = f32_to_bf16_rne(o0 * inv) | (f32_to_bf16_rne(o1 * inv) << 16);
+  const f32x2 r = {o0 * inv, o1 * inv};
+  *dst = __builtin_bit_cast(uint32_t, __builtin_convertvector(r, bf16x2));
 }
 
 }  // namespace

@@ -11,7 +11,7 @@ typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));  // one 16-byte lane
 
 constexpr int kHeadDim = 128;       // D
 constexpr int kBlockTokens = 16;    // B
-constexpr int kMaxPartition = 4096; // tokens; bounds the LDS block-id stage
+constexpr int kMaxPartition = 1024; // tokens: 64 blocks, one block id per lane of a wavefront
 constexpr int kMaxGroup = 16;       // query heads per KV head
 
 struct AttnLaunch {

@@ -46,12 +46,12 @@ def test_partition_and_workspace():
     assert pkv.pkv_attn_workspace_bytes(sh) == 0
     sh = pkv.make_shape(4, 8, 2, 19, 128)
     P = pkv.pkv_attn_partition_size(sh)
-    assert P % 16 == 0 and 16 <= P <= 4096
+    assert P % 16 == 0 and 16 <= P <= 1024
 
 
 @pytest.mark.parametrize("kw", [
     dict(head_dim=64), dict(block_size=32), dict(num_q_heads=9), dict(num_kv_heads=0),
-    dict(partition_size=24), dict(partition_size=8192), dict(partition_size=-16),
+    dict(partition_size=24), dict(partition_size=2048), dict(partition_size=-16),
     dict(max_blocks_per_seq=0), dict(num_seqs=-1), dict(max_context_len=20 * 16),
     dict(max_context_len=-1), dict(num_pool_blocks=0), dict(num_pool_blocks=2 ** 31),
 ])

@@ -59,7 +59,7 @@ def test_partition_size_invariance(device):
     w = wl.custom([1300, 700, 45, 2048], 40, 8, seed=5)
     q, k, v = wl.make_host_tensors(w)
     outs = {}
-    for P in (16, 128, 512, 4096, 0):
+    for P in (16, 128, 512, 1024, 0):
         outs[P] = run_attn(w, q, k, v, partition_size=P)
         check(w, q, k, v, outs[P], f"P={P}")
     a = wl.bf16_bits_to_f64(outs[16])
