@@ -37,19 +37,21 @@ extern "C" {
  * (continuous batching, paper Section II-B), so nothing here is fixed at
  * library start-up. */
 typedef struct {
-  int32_t num_seqs;           /* S: requests in this step's batch (0 is allowed)        */
+  int32_t num_seqs;           /* S: requests in this step's batch, 0..4096              */
   int32_t num_q_heads;        /* Hq                                                      */
   int32_t num_kv_heads;       /* Hkv; Hq % Hkv == 0; query heads h*G..h*G+G-1 share
                                  KV head h (G = Hq/Hkv, 1 <= G <= 16)                    */
   int32_t head_dim;           /* D: 128                                                  */
   int32_t block_size;         /* B: 16 tokens per physical block                         */
   int32_t max_blocks_per_seq; /* MAXB: row stride of block_tables, >= ceil(L_s/B)        */
-  int32_t partition_size;     /* split-K partition in tokens: a multiple of B in
-                                 [B, 1024], or 0 to let the library choose               */
+  int32_t partition_size;     /* P: most tokens of a request that one partial result may
+                                 cover before the split-K merge: a multiple of B in
+                                 [B, 65536], or 0 to let the library choose              */
   int32_t max_context_len;    /* host upper bound on every context_lens[s]; 0 means
                                  MAXB*B.  A smaller bound only shrinks the launch;
                                  a request longer than the bound is attended up to it.   */
-  int64_t num_pool_blocks;    /* NB: physical blocks in k_pool and in v_pool, 1..2^31-1  */
+  int64_t num_pool_blocks;    /* NB: physical blocks in k_pool and in v_pool;
+                                 1 <= NB and NB * Hkv < 2^31                             */
 } pkv_attn_shape;
 
 /* The split-K partition size (tokens) a call with this shape will use:
@@ -57,8 +59,8 @@ typedef struct {
  * Returns a negative status on a bad shape. */
 int pkv_attn_partition_size(const pkv_attn_shape* shape /* host */);
 
-/* Bytes of device workspace paged_decode_attn needs for this shape (0 when one
- * partition covers max_context_len).  `out_bytes` is host memory. */
+/* Bytes of device workspace paged_decode_attn needs for this shape (0 only for
+ * an empty batch).  `out_bytes` is host memory. */
 int pkv_attn_workspace_bytes(const pkv_attn_shape* shape /* host */, size_t* out_bytes);
 
 /*
@@ -82,7 +84,10 @@ int pkv_attn_workspace_bytes(const pkv_attn_shape* shape /* host */, size_t* out
  *
  * Arithmetic: bf16 inputs, fp32 scores, softmax statistics and accumulation,
  * one round-to-nearest-even to bf16 at the end.  The result does not depend on
- * which physical blocks hold the rows, nor on the other requests in the batch.
+ * which physical blocks hold the rows.  The work is spread evenly over the GPU
+ * by cutting the batch's KV blocks into equal shares, so where a request's
+ * partial sums are split (and with it the last bits of its row) depends on the
+ * lengths of the requests ahead of it in the batch.
  *
  *   q            device  bf16  [S][Hq][D]
  *   k_pool       device  bf16  [NB][Hkv][B][D]
@@ -94,7 +99,8 @@ int pkv_attn_workspace_bytes(const pkv_attn_shape* shape /* host */, size_t* out
  *   shape        host
  *   workspace    device, >= pkv_attn_workspace_bytes(), 16-byte aligned; may be
  *                NULL when that size is 0.  Contents need no initialisation and
- *                are undefined afterwards.
+ *                are undefined afterwards.  Calls that overlap in time need
+ *                separate workspaces.
  *   stream       hipStream_t (NULL = the default stream)
  */
 int paged_decode_attn(const void* q, const void* k_pool, const void* v_pool,

@@ -1,9 +1,10 @@
-// Split-K merge for paged decode attention on gfx950: combines the per-partition
-// (running max, partial sum, un-normalised output) triples of one (request,
-// query head) into the final bf16 row.  The maxima are in log2 units, as the
-// partition pass leaves them.  One wavefront per row; the lanes fetch the
-// partitions' statistics side by side, then stream the partial rows eight at a
-// time so that the pass is not a chain of dependent loads.
+// Split-K merge for paged decode attention on gfx950: combines the partial
+// records (reference max, partial sum, un-normalised row) that the stream pass
+// left for one (request, query head) into the final bf16 row.  The maxima are in
+// log2 units.  One wavefront per row; the lanes fetch the records' statistics
+// side by side, then stream the partial rows eight at a time so that the pass
+// is not a chain of dependent loads.  Which slots hold a segment's records
+// follows from the stream layout described in pkv_kernels.h.
 #include "pkv_kernels.h"
 
 namespace pkv {
@@ -32,16 +33,27 @@ __global__ __launch_bounds__(kRowsPerGroup * 64) void attn_reduce_kernel(AttnLau
   if (row >= a.S * a.Hq) return;
   const int lane = threadIdx.x & 63;
   const int s = row / a.Hq, h = row - s * a.Hq;
-  const int L = min(max(a.context_lens[s], 0), a.max_ctx);
-  const int np = (L + a.P - 1) / a.P;   // partitions that were written
+  const int kvh = h / a.G, g = h - kvh * a.G;
+  const int* cumB = a.ws_cum;
+  const int* cumNP = a.ws_cum + (a.S + 1);
+  const int nb = cumB[s + 1] - cumB[s];
   uint32_t* dst = (uint32_t*)(a.out + (int64_t)row * kHeadDim) + lane;
-  if (np <= 0) { *dst = 0u; return; }
+  if (nb <= 0) { *dst = 0u; return; }   // an empty request owes a zero row
 
-  const int64_t base = ((int64_t)s * a.NP) * a.Hq + h;   // + p*Hq per partition
+  const int64_t T = (int64_t)a.Hkv * cumB[a.S];
+  const int64_t W = min((int64_t)kStreamWaves, T);
+  const int nps = cumNP[s + 1] - cumNP[s];
+  const int64_t pos_a = (int64_t)a.Hkv * cumB[s] + (int64_t)kvh * nb;   // the segment's first block
+  const int gp0 = a.Hkv * cumNP[s] + kvh * nps;
+  const int first = gp0 + share_owner(pos_a, T, W);
+  const int last = gp0 + (nps - 1) + share_owner(pos_a + nb - 1, T, W);
+  const int np = last - first + 1;   // records of this row, a neutral filler possibly among them
+
+  auto rec = [&](int p) -> int64_t { return (int64_t)(first + p) * a.G + g; };
   float M = kNegInf;
   for (int p0 = 0; p0 < np; p0 += 64) {
     const int p = p0 + lane;
-    if (p < np) M = fmaxf(M, a.ws_ml[base + (int64_t)p * a.Hq].x);
+    if (p < np) M = fmaxf(M, a.ws_ml[rec(p)].x);
   }
   M = wave_max(M);
 
@@ -50,8 +62,8 @@ __global__ __launch_bounds__(kRowsPerGroup * 64) void attn_reduce_kernel(AttnLau
     const int p = p0 + lane;
     float w = 0.f;
     if (p < np) {
-      const float2 ml = a.ws_ml[base + (int64_t)p * a.Hq];
-      // A partition whose blocks were all unmapped carries max = -inf, sum = 0.
+      const float2 ml = a.ws_ml[rec(p)];
+      // A record whose blocks were all unmapped, or a filler, carries max = -inf, sum = 0.
       w = (ml.x == kNegInf) ? 0.f : __builtin_amdgcn_exp2f(ml.x - M);
       lsum = __builtin_fmaf(w, ml.y, lsum);
     }
@@ -63,12 +75,13 @@ __global__ __launch_bounds__(kRowsPerGroup * 64) void attn_reduce_kernel(AttnLau
       for (int u = 0; u < kBatch; ++u) {
         const int j = min(j0 + u, cnt - 1);   // clamped rows get weight 0
         wj[u] = (j0 + u < cnt) ? __int_as_float(__builtin_amdgcn_readlane(__float_as_int(w), j)) : 0.f;
-        v[u] = *((const float2*)(a.ws_acc + (base + (int64_t)(p0 + j) * a.Hq) * kHeadDim) + lane);
+        v[u] = *((const float2*)(a.ws_acc + rec(p0 + j) * kHeadDim) + lane);
       }
 #pragma unroll
       for (int u = 0; u < kBatch; ++u) {
-        o0 = __builtin_fmaf(wj[u], v[u].x, o0);
-        o1 = __builtin_fmaf(wj[u], v[u].y, o1);
+        // a weight of exactly zero must also silence whatever the row holds
+        o0 = (wj[u] != 0.f) ? __builtin_fmaf(wj[u], v[u].x, o0) : o0;
+        o1 = (wj[u] != 0.f) ? __builtin_fmaf(wj[u], v[u].y, o1) : o1;
       }
     }
   }

@@ -1,0 +1,340 @@
+// Paged decode attention, stream pass, for gfx950 (wave64, MFMA).
+//
+// Decode attends over every running request's whole KV cache and is bound by
+// memory bandwidth (paper Section II-A), and the batch mixes short answering
+// contexts with long reasoning ones (Section III), so equal work per wavefront
+// cannot come from a per-request grid.  Instead the batch's KV blocks form one
+// stream (layout in pkv_kernels.h) that is cut into kStreamWaves equal shares:
+// every wavefront reads the same number of blocks (+-1), starts streaming at
+// once, never idles between requests, and there is no tail of late workgroups.
+// A wavefront emits one partial record per run (a stretch of its share inside
+// one request, one KV head and one P-token partition); the merge pass combines
+// the records of each (request, query head).
+//
+// Per 16-token block, lane = 16*c + n:
+//   S^T = K . Q^T   four v_mfma_f32_16x16x32_bf16 (k = 32 dims each).
+//         A = K rows: lane (n, c) loads the 16 bytes at dims 32*jj + 8*c of
+//         token tau(n) = 4*(n%4) + n/4, straight from the pool (a 64-byte run
+//         per token per load).  B = q: lane (n, c) holds the same dims of head n
+//         (the GQA group padded to 16 rows).  The result leaves lane (n, c)
+//         with head n's scores for tokens 4*i + c.
+//   P     = exp2(score - m) in fp32, split into bf16 hi + lo parts so that the
+//         weights keep ~16 mantissa bits through the second product.
+//   O    += P . V   eight v_mfma_f32_16x16x16_bf16 per part.  V is loaded in its
+//         natural order (lane (n, c) gets dims 8n..8n+7 of tokens 4*e + c, four
+//         fully contiguous 1 KiB loads); the operand for output dims 8*n + i
+//         pairs up the i-th halves of those four loads with v_perm_b32.  The
+//         token order 4*e + c is exactly the one the scores came out in, so P
+//         needs no shuffle between the two products.
+// The running maximum m is only raised when a score exceeds it by more than
+// 2^kLazyLog2; any reference value gives the same softmax, and the bound keeps
+// every weight within fp32/bf16 range.
+//
+// Where a block lives (physical id, KV head), how many of its tokens are valid
+// and whether it closes a run is worked out 64 blocks at a time, one block per
+// lane ("descriptors"), one window ahead of use; the streaming loop itself only
+// reads a lane of those registers per block, so no memory access sits on the
+// address path of the KV loads.
+#include "pkv_kernels.h"
+
+namespace pkv {
+namespace {
+
+#ifndef PKV_RING
+#define PKV_RING 4
+#endif
+constexpr int kRing = PKV_RING;   // 16-token blocks in flight per wavefront (register ring)
+constexpr int kWindow = 64;       // descriptors per window: one per lane
+static_assert(kWindow % kRing == 0, "the window must be a whole number of ring turns");
+constexpr float kNegInf = -__builtin_huge_valf();
+constexpr float kLazyLog2 = 8.f;
+
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
+typedef short s16x4 __attribute__((ext_vector_type(4)));
+typedef float f32x4 __attribute__((ext_vector_type(4)));
+typedef float f32x2 __attribute__((ext_vector_type(2)));
+typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
+
+// Two fp32 -> packed bf16, round to nearest even (v_cvt_pk_bf16_f32).
+__device__ __forceinline__ uint32_t pack_bf16(float lo, float hi) {
+  const f32x2 f = {lo, hi};
+  return __builtin_bit_cast(uint32_t, __builtin_convertvector(f, bf16x2));
+}
+// The same rounding, then the fp32 value of what was kept.
+__device__ __forceinline__ float bf16_round(float x, uint32_t& bits) {
+  bits = pack_bf16(x, 0.f) & 0xffffu;
+  return __uint_as_float(bits << 16);
+}
+
+// One window of block descriptors: lane i describes stream index jbase + i.
+struct Window {
+  int slab;   // phys * Hkv + kvh: which 4 KiB (block, KV head) slab; 0 when the block is not read
+  int meta;   // bits 0-7 valid tokens (0..16), bit 8 closes a run, bit 9 first block of a segment here
+  int qrow;   // s * Hq + kvh * G: first query/output row of the segment
+  int slot;   // partial-record slot of the run this block belongs to
+};
+constexpr int kMetaLast = 1 << 8;
+constexpr int kMetaSegFirst = 1 << 9;
+
+__global__ __launch_bounds__(kStreamWavesPerGroup * 64) void attn_stream_kernel(AttnLaunch a) {
+  extern __shared__ int smem[];
+  int* cumB = smem;                  // [S+1] blocks before request s
+  int* cumNP = smem + (a.S + 1);     // [S+1] partitions before request s
+  int* lens = smem + 2 * (a.S + 1);  // [S]   clamped context lengths
+
+  const int wave = threadIdx.x >> 6;
+  const int lane = threadIdx.x & 63;
+  const int n = lane & 15, c = lane >> 4;
+  const int G = a.G, S = a.S, Hkv = a.Hkv;
+  const int bpp = a.P / kBlockTokens;   // blocks per partition
+
+  // Prefix sums over the requests (wavefront 0 of every workgroup; S is small).
+  if (wave == 0) {
+    int runB = 0, runP = 0;
+    for (int base = 0; base < S; base += 64) {
+      const int i = base + lane;
+      const int L = (i < S) ? min(max(a.context_lens[i], 0), a.max_ctx) : 0;
+      const int nb = (L + kBlockTokens - 1) / kBlockTokens;
+      const int np = (nb + bpp - 1) / bpp;
+      int xb = nb, xp = np;
+#pragma unroll
+      for (int o = 1; o < 64; o <<= 1) {
+        const int yb = __shfl_up(xb, o), yp = __shfl_up(xp, o);
+        if (lane >= o) { xb += yb; xp += yp; }
+      }
+      if (i < S) { lens[i] = L; cumB[i] = runB + xb - nb; cumNP[i] = runP + xp - np; }
+      runB += __shfl(xb, 63);
+      runP += __shfl(xp, 63);
+    }
+    if (lane == 0) { cumB[S] = runB; cumNP[S] = runP; }
+  }
+  __syncthreads();
+  if (blockIdx.x == 0) {   // the merge pass reads the same prefix arrays
+    for (int i = threadIdx.x; i < 2 * (S + 1); i += blockDim.x) a.ws_cum[i] = smem[i];
+  }
+
+  // Every participating wavefront gets at least one block, so that consecutive
+  // runs of a segment always belong to the same or to adjacent wavefronts.
+  const int64_t T = (int64_t)Hkv * cumB[S];
+  const int W = (int)min((int64_t)kStreamWaves, T);
+  const int w = blockIdx.x * kStreamWavesPerGroup + wave;
+  if (w >= W) return;
+  const int pos0 = (int)share_start(w, T, W);
+  const int nshare = (int)share_start(w + 1, T, W) - pos0;
+
+  // Descriptors of stream indices jb .. jb+63 of this share.
+  int search_steps = 0;
+  while ((1 << search_steps) < S) ++search_steps;
+  auto describe = [&](int jb) -> Window {
+    const int j = jb + lane;
+    const bool live = j < nshare;
+    const int pos = pos0 + min(j, nshare - 1);
+    int lo = 0, hi = S;   // largest s with Hkv * cumB[s] <= pos
+    for (int it = 0; it < search_steps; ++it) {
+      const int mid = (lo + hi) >> 1;
+      if (mid > lo && Hkv * cumB[mid] <= pos) lo = mid; else if (mid > lo) hi = mid;
+    }
+    const int s = lo;
+    const int nb = cumB[s + 1] - cumB[s];
+    const int o = pos - Hkv * cumB[s];
+    const int kvh = o / nb;
+    const int b = o - kvh * nb;
+    const int nps = cumNP[s + 1] - cumNP[s];
+    int ntok = min(kBlockTokens, lens[s] - kBlockTokens * b);
+    const int id = live ? a.block_tables[(int64_t)s * a.MAXB + b] : -1;
+    const bool mapped = (unsigned)id < (unsigned)a.NB;   // ids outside the pool are never followed
+    if (!mapped) ntok = 0;
+    Window d;
+    d.slab = mapped ? id * Hkv + kvh : 0;
+    const bool last = (b + 1 == nb) || ((b + 1) % bpp == 0) || (j + 1 == nshare);
+    const bool seg_first = (b == 0) || (j == 0);
+    d.meta = ntok | (last ? kMetaLast : 0) | (seg_first ? kMetaSegFirst : 0);
+    d.qrow = s * a.Hq + kvh * G;
+    d.slot = Hkv * cumNP[s] + kvh * nps + b / bpp + w;
+    return d;
+  };
+
+  Window dA = describe(0);
+  Window dB = describe(kWindow);
+  int jbase = 0;
+
+  // When this share begins exactly on a partition boundary the previous
+  // wavefront's last slot and this one's first differ by two; the slot between
+  // them belongs to nobody and is given a neutral record so that the merge may
+  // walk a segment's slots without gaps.
+  {
+    const int slot0 = __builtin_amdgcn_readfirstlane(dA.slot);
+    const int qrow0 = __builtin_amdgcn_readfirstlane(dA.qrow);
+    const int s0 = qrow0 / a.Hq;
+    const int kvh0 = (qrow0 - s0 * a.Hq) / G;
+    const int b0 = (pos0 - Hkv * cumB[s0]) - kvh0 * (cumB[s0 + 1] - cumB[s0]);
+    if (w > 0 && b0 > 0 && b0 % bpp == 0 && lane < G)
+      a.ws_ml[(int64_t)(slot0 - 1) * G + lane] = make_float2(kNegInf, 0.f);
+  }
+
+  const int64_t head_elems = (int64_t)kBlockTokens * kHeadDim;  // one (block, KV head) slab
+  const int tau = 4 * (n & 3) + (n >> 2);
+  const int koff = tau * 16 + c;   // in 16-byte units within the slab
+
+  u32x4 qop[4];        // q as the B operand: dims 32*jj + 8*c .. +7 of head n; zero rows beyond the group
+  float m = kNegInf;   // running reference maximum of head n (log2 units), same in all four c groups
+  float l = 0.f;       // this lane's share of the softmax denominator
+  f32x4 o[8];          // o[i][r]: head 4*c + r, dim 8*n + i
+#pragma unroll
+  for (int i = 0; i < 8; ++i) o[i] = f32x4{0.f, 0.f, 0.f, 0.f};
+
+  // Issue the eight 16-byte loads of stream index j (K in operand order, V
+  // natural).  The loads are unconditional so that every wait in the loop knows
+  // exactly how many are outstanding: a block that is unmapped, or an index past
+  // the share's end, reads slab 0 (which always exists) and is masked or skipped.
+  auto issue = [&](u32x4 (&k)[4], u32x4 (&v)[4], int j) {
+    const int idx = j - jbase;   // 0 .. 2*kWindow-1
+    const int sa = __builtin_amdgcn_readlane(dA.slab, idx & (kWindow - 1));
+    const int sb = __builtin_amdgcn_readlane(dB.slab, idx & (kWindow - 1));
+    int slab = (idx < kWindow) ? sa : sb;
+    if (j >= nshare) slab = 0;
+    const int64_t base = (int64_t)slab * head_elems;
+    const u32x4* kp = (const u32x4*)(a.k_pool + base) + koff;
+    const u32x4* vp = (const u32x4*)(a.v_pool + base) + lane;
+#pragma unroll
+    for (int jj = 0; jj < 4; ++jj) k[jj] = kp[4 * jj];
+#pragma unroll
+    for (int jj = 0; jj < 4; ++jj) v[jj] = vp[64 * jj];
+  };
+
+  auto consume = [&](u32x4 (&k)[4], u32x4 (&v)[4], int j) {
+    const int idx = j - jbase;   // always inside window A
+    const int meta = __builtin_amdgcn_readlane(dA.meta, idx);
+    const int ntok = meta & 0xff;
+
+    if (meta & kMetaSegFirst) {
+      // A new (request, KV head): fetch its query group.
+      const int qrow = __builtin_amdgcn_readlane(dA.qrow, idx);
+      const u32x4* qp = (const u32x4*)(a.q + (int64_t)(qrow + min(n, G - 1)) * kHeadDim) + c;
+#pragma unroll
+      for (int jj = 0; jj < 4; ++jj) {
+        const u32x4 wq = qp[4 * jj];
+        qop[jj] = (n < G) ? wq : u32x4{0, 0, 0, 0};
+      }
+    }
+
+    f32x4 sc = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+    for (int jj = 0; jj < 4; ++jj)
+      sc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, k[jj]),
+                                                   __builtin_bit_cast(bf16x8, qop[jj]), sc, 0, 0, 0);
+    float x[4] = {sc.x * a.scale_log2e, sc.y * a.scale_log2e, sc.z * a.scale_log2e,
+                  sc.w * a.scale_log2e};
+    const bool edge = ntok < kBlockTokens;
+    bool valid[4] = {true, true, true, true};
+    if (edge) {
+      // Last block of a request, or an unmapped one: masked slots may hold anything
+      // (NaN included), so scores, weights and V rows are replaced by select,
+      // never scaled by zero.  Element e of this lane is token 4*e + c.
+#pragma unroll
+      for (int e = 0; e < 4; ++e) {
+        valid[e] = 4 * e + c < ntok;
+        x[e] = valid[e] ? x[e] : kNegInf;
+        if (!valid[e]) v[e] = u32x4{0, 0, 0, 0};
+      }
+    }
+    const float mx = fmaxf(fmaxf(x[0], x[1]), fmaxf(x[2], x[3]));
+    if (__any(mx > m + kLazyLog2)) {
+      float mg = fmaxf(mx, __shfl_xor(mx, 16));
+      mg = fmaxf(mg, __shfl_xor(mg, 32));
+      const float mnew = fmaxf(m, mg);   // finite: some lane of the head saw a valid token
+      const float alpha = __builtin_amdgcn_exp2f(m - mnew);
+      l *= alpha;
+      float ar[4];
+#pragma unroll
+      for (int r = 0; r < 4; ++r) ar[r] = __shfl(alpha, 4 * c + r);
+#pragma unroll
+      for (int i = 0; i < 8; ++i) {
+        o[i].x *= ar[0]; o[i].y *= ar[1]; o[i].z *= ar[2]; o[i].w *= ar[3];
+      }
+      m = mnew;
+    }
+    float pw[4];
+#pragma unroll
+    for (int e = 0; e < 4; ++e) pw[e] = __builtin_amdgcn_exp2f(x[e] - m);
+    if (edge) {
+#pragma unroll
+      for (int e = 0; e < 4; ++e) pw[e] = valid[e] ? pw[e] : 0.f;   // m may still be -inf here
+    }
+    l += (pw[0] + pw[1]) + (pw[2] + pw[3]);
+
+    // P = hi + lo in bf16.
+    uint32_t hb[4];
+    float lo[4];
+#pragma unroll
+    for (int e = 0; e < 4; ++e) lo[e] = pw[e] - bf16_round(pw[e], hb[e]);
+    const u32x2 phi = {hb[0] | (hb[1] << 16), hb[2] | (hb[3] << 16)};
+    const u32x2 plo = {pack_bf16(lo[0], lo[1]), pack_bf16(lo[2], lo[3])};
+    const s16x4 pa = __builtin_bit_cast(s16x4, phi);
+    const s16x4 pb = __builtin_bit_cast(s16x4, plo);
+#pragma unroll
+    for (int i = 0; i < 8; ++i) {
+      const int wsel = i >> 1;
+      const uint32_t sel = (i & 1) ? 0x07060302u : 0x05040100u;
+      const u32x2 vb = {__builtin_amdgcn_perm(v[1][wsel], v[0][wsel], sel),
+                        __builtin_amdgcn_perm(v[3][wsel], v[2][wsel], sel)};
+      const s16x4 vop = __builtin_bit_cast(s16x4, vb);
+      o[i] = __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(pa, vop, o[i], 0, 0, 0);
+      o[i] = __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(pb, vop, o[i], 0, 0, 0);
+    }
+
+    if (meta & kMetaLast) {
+      // The run ends here: store its partial record and start afresh.
+      const int slot = __builtin_amdgcn_readlane(dA.slot, idx);
+      float lt = l + __shfl_xor(l, 16);
+      lt += __shfl_xor(lt, 32);
+#pragma unroll
+      for (int r = 0; r < 4; ++r) {
+        const int h = 4 * c + r;
+        if (h < G) {
+          float4* dst = (float4*)(a.ws_acc + ((int64_t)slot * G + h) * kHeadDim + 8 * n);
+          dst[0] = make_float4(o[0][r], o[1][r], o[2][r], o[3][r]);
+          dst[1] = make_float4(o[4][r], o[5][r], o[6][r], o[7][r]);
+        }
+      }
+      if (c == 0 && n < G) a.ws_ml[(int64_t)slot * G + n] = make_float2(m, lt);
+      m = kNegInf;
+      l = 0.f;
+#pragma unroll
+      for (int i = 0; i < 8; ++i) o[i] = f32x4{0.f, 0.f, 0.f, 0.f};
+    }
+  };
+
+  // A ring of kRing register buffers: kRing - 1 blocks are always in flight
+  // while one is consumed, and no buffer is ever copied.
+  u32x4 kbuf[kRing][4], vbuf[kRing][4];
+#pragma unroll
+  for (int i = 0; i < kRing - 1; ++i) issue(kbuf[i], vbuf[i], i);
+  for (int j = 0; j < nshare; j += kRing) {
+#pragma unroll
+    for (int i = 0; i < kRing; ++i) {
+      constexpr int kAhead = kRing - 1;
+      issue(kbuf[(i + kAhead) % kRing], vbuf[(i + kAhead) % kRing], j + i + kAhead);
+      if (j + i < nshare) consume(kbuf[i], vbuf[i], j + i);
+    }
+    if (j + kRing == jbase + kWindow) {
+      // The consumer leaves window A: B becomes A, and the window after it is
+      // described now, 64 blocks before its first use.
+      dA = dB;
+      jbase += kWindow;
+      dB = describe(jbase + kWindow);
+    }
+  }
+}
+
+}  // namespace
+
+hipError_t launch_attn_stream(const AttnLaunch& a, hipStream_t stream) {
+  const size_t lds = (size_t)(3 * (a.S + 1)) * sizeof(int);
+  hipLaunchKernelGGL(attn_stream_kernel, dim3(kStreamGroups), dim3(kStreamWavesPerGroup * 64), lds,
+                     stream, a);
+  return hipGetLastError();
+}
+
+}  // namespace pkv

@@ -10,19 +10,20 @@ thread_local hipError_t g_last_launch_error = hipSuccess;
 
 inline bool misaligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) != 0; }
 
-// Library's split-K partition choice when the caller leaves it open: small
-// enough that (requests x KV heads x partitions) oversubscribes 256 CUs several
-// times at batch sizes of a few dozen, large enough that the per-partition
-// epilogue (a 520-byte row per query head) stays near 1 % of the KV it stands for.
-constexpr int kDefaultPartition = 256;
+// Library's partition choice when the caller leaves it open.  With the stream
+// decomposition a partition only bounds how many tokens one partial record may
+// stand for, so a large value costs nothing but the record it closes.
+constexpr int kDefaultPartition = 1024;
 
 struct Geometry {
-  int G, P, NP, max_ctx;
+  int G, P, max_ctx;
+  int64_t slots;   // upper bound on partial-record slots
 };
 
 int check_shape(const pkv_attn_shape* sh, Geometry* g) {
   if (!sh) return PKV_ERR_NULL;
-  if (sh->num_seqs < 0 || sh->num_q_heads <= 0 || sh->num_kv_heads <= 0) return PKV_ERR_SHAPE;
+  if (sh->num_seqs < 0 || sh->num_seqs > pkv::kMaxSeqs) return PKV_ERR_SHAPE;
+  if (sh->num_q_heads <= 0 || sh->num_kv_heads <= 0) return PKV_ERR_SHAPE;
   if (sh->head_dim != pkv::kHeadDim || sh->block_size != pkv::kBlockTokens) return PKV_ERR_SHAPE;
   if (sh->num_q_heads % sh->num_kv_heads != 0) return PKV_ERR_SHAPE;
   const int G = sh->num_q_heads / sh->num_kv_heads;
@@ -37,21 +38,38 @@ int check_shape(const pkv_attn_shape* sh, Geometry* g) {
   if (P == 0) P = kDefaultPartition;
   if (P % pkv::kBlockTokens != 0 || P < pkv::kBlockTokens || P > pkv::kMaxPartition)
     return PKV_ERR_SHAPE;
-  if (sh->num_pool_blocks < 1 || sh->num_pool_blocks > INT32_MAX) return PKV_ERR_SHAPE;
-  const int NP = (max_ctx + P - 1) / P;
-  if ((int64_t)sh->num_seqs * NP > INT32_MAX) return PKV_ERR_SHAPE;
+  if (sh->num_pool_blocks < 1 || sh->num_pool_blocks * sh->num_kv_heads > INT32_MAX)
+    return PKV_ERR_SHAPE;
+  // stream positions, slots and rows are 32-bit on the device
+  const int64_t max_blocks = (max_ctx + pkv::kBlockTokens - 1) / pkv::kBlockTokens;
+  if ((int64_t)sh->num_kv_heads * sh->num_seqs * max_blocks > INT32_MAX) return PKV_ERR_SHAPE;
   if ((int64_t)sh->num_seqs * sh->num_q_heads > INT32_MAX) return PKV_ERR_SHAPE;
+  const int64_t NP = (max_ctx + P - 1) / P;
   g->G = G;
   g->P = P;
-  g->NP = NP;
   g->max_ctx = max_ctx;
+  g->slots = (int64_t)sh->num_kv_heads * sh->num_seqs * NP + pkv::kStreamWaves + 1;
+  if (g->slots * G > INT32_MAX) return PKV_ERR_SHAPE;
   return PKV_OK;
 }
 
+// Workspace: partial rows, their (max, sum) pairs, the two prefix arrays.
+struct WorkspaceLayout {
+  size_t acc_bytes, ml_bytes, cum_bytes;
+  size_t total() const { return acc_bytes + ml_bytes + cum_bytes; }
+};
+
+WorkspaceLayout workspace_layout(const pkv_attn_shape* sh, const Geometry& g) {
+  WorkspaceLayout w;
+  const size_t rows = (size_t)g.slots * g.G;
+  w.acc_bytes = rows * pkv::kHeadDim * sizeof(float);
+  w.ml_bytes = (rows * sizeof(float2) + 15) & ~(size_t)15;
+  w.cum_bytes = ((size_t)2 * (sh->num_seqs + 1) * sizeof(int32_t) + 15) & ~(size_t)15;
+  return w;
+}
+
 size_t workspace_bytes(const pkv_attn_shape* sh, const Geometry& g) {
-  if (g.NP <= 1) return 0;
-  const size_t rows = (size_t)sh->num_seqs * g.NP * sh->num_q_heads;
-  return rows * (pkv::kHeadDim * sizeof(float) + sizeof(float2));
+  return sh->num_seqs == 0 ? 0 : workspace_layout(sh, g).total();
 }
 
 int launch_status(hipError_t e) {
@@ -126,22 +144,20 @@ int paged_decode_attn(const void* q, const void* k_pool, const void* v_pool,
   a.G = g.G;
   a.MAXB = shape->max_blocks_per_seq;
   a.P = g.P;
-  a.NP = g.NP;
   a.max_ctx = g.max_ctx;
   a.NB = (int)shape->num_pool_blocks;
   a.scale_log2e = scale * 1.4426950408889634f;
-  const size_t rows = (size_t)a.S * a.NP * a.Hq;
-  a.ws_acc = static_cast<float*>(workspace);
-  a.ws_ml = need ? reinterpret_cast<float2*>(static_cast<float*>(workspace) + rows * pkv::kHeadDim)
-                 : nullptr;
+  const WorkspaceLayout lay = workspace_layout(shape, g);
+  char* ws = static_cast<char*>(workspace);
+  a.ws_acc = reinterpret_cast<float*>(ws);
+  a.ws_ml = reinterpret_cast<float2*>(ws + lay.acc_bytes);
+  a.ws_cum = reinterpret_cast<int32_t*>(ws + lay.acc_bytes + lay.ml_bytes);
 
   hipStream_t st = static_cast<hipStream_t>(stream);
-  hipError_t e = pkv::launch_attn_partition(a, st);
+  hipError_t e = pkv::launch_attn_stream(a, st);
   if (e != hipSuccess) return launch_status(e);
-  if (a.NP > 1) {
-    e = pkv::launch_attn_reduce(a, st);
-    if (e != hipSuccess) return launch_status(e);
-  }
+  e = pkv::launch_attn_reduce(a, st);
+  if (e != hipSuccess) return launch_status(e);
   return PKV_OK;
 }
 

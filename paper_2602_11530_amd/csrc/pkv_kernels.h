@@ -9,10 +9,39 @@ namespace pkv {
 
 typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));  // one 16-byte lane load
 
-constexpr int kHeadDim = 128;       // D
-constexpr int kBlockTokens = 16;    // B
-constexpr int kMaxPartition = 1024; // tokens: 64 blocks, one block id per lane of a wavefront
-constexpr int kMaxGroup = 16;       // query heads per KV head
+constexpr int kHeadDim = 128;        // D
+constexpr int kBlockTokens = 16;     // B
+constexpr int kMaxPartition = 65536; // tokens covered by one partial result, upper bound
+constexpr int kMaxGroup = 16;        // query heads per KV head
+constexpr int kMaxSeqs = 4096;       // per-request prefix arrays live in LDS
+
+// The attention pass is a persistent launch sized for the 256 compute units of
+// an MI355X: two 4-wave workgroups per unit, each wavefront streaming an equal
+// share of the batch's KV blocks.
+#ifndef PKV_STREAM_GROUPS
+#define PKV_STREAM_GROUPS 512
+#endif
+constexpr int kStreamWavesPerGroup = 4;
+constexpr int kStreamGroups = PKV_STREAM_GROUPS;
+constexpr int kStreamWaves = kStreamGroups * kStreamWavesPerGroup;
+
+// How the batch's KV blocks are laid out as one stream and cut into shares.
+//   Segment (s, kvh) holds the nblk_s = ceil(L_s/16) blocks of request s for KV
+//   head kvh; segments follow each other in (s, kvh) order; position pos of the
+//   stream is block b of segment (s, kvh) with
+//       pos = Hkv * cumB[s] + kvh * nblk_s + b,     cumB[s] = sum_{s'<s} nblk_s'.
+//   Wavefront w owns positions [w*T/W, (w+1)*T/W), T = Hkv * cumB[S].
+//   A run is a maximal stretch of one wavefront's share inside one segment and
+//   one partition (P tokens of the request); every run yields one partial record
+//   (max, sum, un-normalised row) per query head of the group, stored at
+//       slot = Hkv * cumNP[s] + kvh * NP_s + p + w,  NP_s = ceil(L_s/P),
+//   which is unique and increases along the stream, so the records of a segment
+//   are the consecutive slots between its first and its last run.
+__host__ __device__ inline int64_t share_start(int64_t w, int64_t T, int64_t W) { return w * T / W; }
+// The wavefront whose share holds position pos.
+__host__ __device__ inline int share_owner(int64_t pos, int64_t T, int64_t W) {
+  return (int)(((pos + 1) * W - 1) / T);
+}
 
 struct AttnLaunch {
   const uint16_t* q;
@@ -21,19 +50,19 @@ struct AttnLaunch {
   const int32_t* block_tables;
   const int32_t* context_lens;
   uint16_t* out;
-  float* ws_acc;   // [S][NP][Hq][D] un-normalised partial outputs
-  float2* ws_ml;   // [S][NP][Hq]    (running max in log2 units, partial sum)
+  float* ws_acc;   // [slots * G][D]  un-normalised partial outputs
+  float2* ws_ml;   // [slots * G]     (reference max in log2 units, partial sum)
+  int32_t* ws_cum; // [2 * (S + 1)]   cumB then cumNP, written by the stream pass for the merge
   float scale_log2e;
   int S, Hq, Hkv, G, MAXB;
   int P;           // partition size, tokens
-  int NP;          // partitions launched per request = ceil(max_context_len / P)
   int max_ctx;     // context lengths are clamped to [0, max_ctx] (<= MAXB * 16)
   int NB;          // physical blocks per pool; ids outside [0, NB) are never followed
 };
 
-// Partition kernel: one wavefront per (request, KV head, partition).
-hipError_t launch_attn_partition(const AttnLaunch& a, hipStream_t stream);
-// Split-K merge: one wavefront per (request, query head); only when NP > 1.
+// Stream pass: kStreamWaves persistent wavefronts, each writing its runs' partial records.
+hipError_t launch_attn_stream(const AttnLaunch& a, hipStream_t stream);
+// Merge: one wavefront per (request, query head).
 hipError_t launch_attn_reduce(const AttnLaunch& a, hipStream_t stream);
 
 // Whole-block copies; `gather` selects the direction.

