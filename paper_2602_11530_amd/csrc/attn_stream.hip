@@ -67,6 +67,22 @@ __device__ __forceinline__ float bf16_round(float x, uint32_t& bits) {
   return __uint_as_float(bits << 16);
 }
 
+// Stores of a finished run's record.  They are written as opaque instructions on
+// purpose: gfx9-family hardware counts loads and stores in one counter, and once
+// the compiler knows a store is pending it can no longer wait for "all but the N
+// youngest loads" and drains the whole ring of KV loads at the next use.  Hidden
+// from that bookkeeping, a wait sized for the loads alone is still sufficient
+// (loads retire in order among themselves, so extra pending stores only make the
+// same wait stricter), and the record itself is only read by the next kernel.
+__device__ __forceinline__ void store_record16(float* p, f32x4 v) {
+  // the trailing s_nop covers the wait states a wide store needs before a vector
+  // op may overwrite its data registers (the compiler cannot see that this is a store)
+  asm volatile("global_store_dwordx4 %0, %1, off\n\ts_nop 1" : : "v"(p), "v"(v) : "memory");
+}
+__device__ __forceinline__ void store_record8(float2* p, f32x2 v) {
+  asm volatile("global_store_dwordx2 %0, %1, off\n\ts_nop 1" : : "v"(p), "v"(v) : "memory");
+}
+
 // One window of block descriptors: lane i describes stream index jbase + i.
 struct Window {
   int slab;   // phys * Hkv + kvh: which 4 KiB (block, KV head) slab; 0 when the block is not read
@@ -293,12 +309,12 @@ __global__ __launch_bounds__(kStreamWavesPerGroup * 64) void attn_stream_kernel(
       for (int r = 0; r < 4; ++r) {
         const int h = 4 * c + r;
         if (h < G) {
-          float4* dst = (float4*)(a.ws_acc + ((int64_t)slot * G + h) * kHeadDim + 8 * n);
-          dst[0] = make_float4(o[0][r], o[1][r], o[2][r], o[3][r]);
-          dst[1] = make_float4(o[4][r], o[5][r], o[6][r], o[7][r]);
+          float* dst = a.ws_acc + ((int64_t)slot * G + h) * kHeadDim + 8 * n;
+          store_record16(dst, f32x4{o[0][r], o[1][r], o[2][r], o[3][r]});
+          store_record16(dst + 4, f32x4{o[4][r], o[5][r], o[6][r], o[7][r]});
         }
       }
-      if (c == 0 && n < G) a.ws_ml[(int64_t)slot * G + n] = make_float2(m, lt);
+      if (c == 0 && n < G) store_record8(a.ws_ml + (int64_t)slot * G + n, f32x2{m, lt});
       m = kNegInf;
       l = 0.f;
 #pragma unroll

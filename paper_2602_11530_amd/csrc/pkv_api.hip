@@ -13,7 +13,7 @@ inline bool misaligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p)
 // Library's partition choice when the caller leaves it open.  With the stream
 // decomposition a partition only bounds how many tokens one partial record may
 // stand for, so a large value costs nothing but the record it closes.
-constexpr int kDefaultPartition = 1024;
+constexpr int kDefaultPartition = pkv::kMaxPartition;
 
 struct Geometry {
   int G, P, max_ctx;
