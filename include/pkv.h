@@ -120,7 +120,7 @@ int paged_decode_attn(const void* q, const void* k_pool, const void* v_pool,
  *              skipped on the device (its staging image is left as it was)
  *   staging    device, n_blocks * block_bytes bytes, contiguous, must not
  *              overlap the listed blocks
- *   block_bytes  multiple of 16
+ *   block_bytes  multiple of 16, at most 1 GiB
  *   n_blocks == 0 is a no-op returning PKV_OK.
  */
 int kv_blocks_gather(const void* pool, const int32_t* block_ids, void* staging,

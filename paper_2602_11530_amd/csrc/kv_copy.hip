@@ -7,8 +7,27 @@
 namespace pkv {
 namespace {
 
-constexpr int kCopyThreads = 256;
-constexpr int kChunksPerThread = 8;                               // 16-byte chunks
+#ifndef PKV_COPY_NT
+#define PKV_COPY_NT 3
+#endif
+#if PKV_COPY_NT & 1
+#define PKV_COPY_LOAD(p) __builtin_nontemporal_load(p)
+#else
+#define PKV_COPY_LOAD(p) (*(p))
+#endif
+#if PKV_COPY_NT & 2
+#define PKV_COPY_STORE(v, p) __builtin_nontemporal_store(v, p)
+#else
+#define PKV_COPY_STORE(v, p) (*(p) = (v))
+#endif
+#ifndef PKV_COPY_THREADS
+#define PKV_COPY_THREADS 256
+#endif
+#ifndef PKV_COPY_CHUNKS
+#define PKV_COPY_CHUNKS 8
+#endif
+constexpr int kCopyThreads = PKV_COPY_THREADS;
+constexpr int kChunksPerThread = PKV_COPY_CHUNKS;                               // 16-byte chunks
 constexpr int kChunksPerGroup = kCopyThreads * kChunksPerThread;  // 32 KiB per workgroup
 
 // blockIdx.x = index into block_ids, blockIdx.y = 32 KiB slice of that block.
@@ -26,16 +45,20 @@ __global__ __launch_bounds__(kCopyThreads) void kv_block_copy_kernel(
   const u32x4* s = src + (kGather ? pool_base : stage_base);
   u32x4* d = dst + (kGather ? stage_base : pool_base);
   const int64_t c0 = (int64_t)blockIdx.y * kChunksPerGroup + threadIdx.x;
-  u32x4 v[kChunksPerThread];
+  if (((int64_t)blockIdx.y + 1) * kChunksPerGroup <= chunks_per_block) {
+    // Whole slice inside the block (always, for 32 KiB blocks): all loads are
+    // issued before the first store, with no per-lane guard in the way.
+    u32x4 v[kChunksPerThread];
 #pragma unroll
-  for (int u = 0; u < kChunksPerThread; ++u) {
-    const int64_t c = c0 + (int64_t)u * kCopyThreads;
-    if (c < chunks_per_block) v[u] = __builtin_nontemporal_load(s + c);
-  }
+    for (int u = 0; u < kChunksPerThread; ++u) v[u] = PKV_COPY_LOAD(s + c0 + (int64_t)u * kCopyThreads);
 #pragma unroll
-  for (int u = 0; u < kChunksPerThread; ++u) {
-    const int64_t c = c0 + (int64_t)u * kCopyThreads;
-    if (c < chunks_per_block) __builtin_nontemporal_store(v[u], d + c);
+    for (int u = 0; u < kChunksPerThread; ++u) PKV_COPY_STORE(v[u], d + c0 + (int64_t)u * kCopyThreads);
+  } else {
+    // Ragged last slice of an odd block size.
+    for (int u = 0; u < kChunksPerThread; ++u) {
+      const int64_t c = c0 + (int64_t)u * kCopyThreads;
+      if (c < chunks_per_block) PKV_COPY_STORE(PKV_COPY_LOAD(s + c), d + c);
+    }
   }
 }
 

@@ -166,7 +166,7 @@ static int copy_call(const void* pool, const void* staging, const int32_t* block
                      void* stream) {
   if (n_blocks < 0 || block_bytes <= 0 || num_pool_blocks < 0) return PKV_ERR_SHAPE;
   if (block_bytes % 16 != 0) return PKV_ERR_ALIGN;
-  if (n_blocks > INT32_MAX || (block_bytes / 16 + 2047) / 2048 > 65535) return PKV_ERR_SHAPE;
+  if (n_blocks > INT32_MAX || block_bytes > ((int64_t)1 << 30)) return PKV_ERR_SHAPE;
   if (n_blocks == 0) return PKV_OK;
   if (!pool || !staging || !block_ids) return PKV_ERR_NULL;
   if (misaligned16(pool) || misaligned16(staging) || (reinterpret_cast<uintptr_t>(block_ids) & 3u))
