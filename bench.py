@@ -175,7 +175,7 @@ def main():
         },
         "roofline": {
             "bound": "hbm",
-            "kernel": "attn_partition_kernel (timed together with the split-K reduce that follows it)",
+            "kernel": "attn_stream_kernel (event-timed together with the small merge kernel that follows it)",
             "achieved": round(attn_gbps, 1), "peak": HBM_PEAK_GBPS, "unit": "GB/s",
             "frac": round(attn_gbps / HBM_PEAK_GBPS, 4),
             "traffic": None,
