@@ -23,6 +23,10 @@ if ROOT not in sys.path:
 
 HBM_PEAK_GBPS = 8000.0   # MI355X published HBM3E bandwidth
 
+# HBM bytes per launch of the stream kernel from rocprofv3 FETCH_SIZE + WRITE_SIZE, each scaled by
+# what the same counter reads for the copy kernel of known size (profiles/attn_stream_cfg2.md).
+MEASURED_TRAFFIC_BYTES = {"cfg2_qwen32b_b64_u1024_8192": 1215693000}
+
 
 def parse():
     ap = argparse.ArgumentParser()
@@ -178,7 +182,7 @@ def main():
             "kernel": "attn_stream_kernel (event-timed together with the small merge kernel that follows it)",
             "achieved": round(attn_gbps, 1), "peak": HBM_PEAK_GBPS, "unit": "GB/s",
             "frac": round(attn_gbps / HBM_PEAK_GBPS, 4),
-            "traffic": None,
+            "traffic": MEASURED_TRAFFIC_BYTES.get(w.name) if args.partition is None else None,
         },
     }
 

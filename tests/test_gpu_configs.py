@@ -1,0 +1,196 @@
+"""Configs 4 and 5 on the GPU: a full-depth phase-mixed batch resident in HBM,
+and a preemption / migration step running next to decode on a second stream.
+
+The oracle cannot hold 199 GB, so parity is checked on seeded samples whose K/V
+blocks are pulled to the host with torch indexing (never through the library)."""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+from paper_2602_11530_amd import binding as pkv
+from paper_2602_11530_amd import workloads as wl
+
+from gpu_util import MAX_ABS, REL_L2, assert_launchable, run_attn_dev, shape_of, to_bits, to_dev
+
+pytestmark = pytest.mark.gpu
+
+
+def fill_layer(w, layer, device):
+    g = torch.Generator(device=device)
+    g.manual_seed(w.seed + 1000 * layer + 17)
+    q = torch.randn(w.q_shape(), generator=g, device=device, dtype=torch.float32).to(torch.bfloat16)
+    pools = []
+    for _ in range(2):
+        p = torch.empty(w.pool_shape(), dtype=torch.bfloat16, device=device)
+        flat = p.view(-1)
+        step = 1 << 28
+        for o in range(0, flat.numel(), step):
+            n = min(step, flat.numel() - o)
+            flat[o:o + n] = torch.randn(n, generator=g, device=device, dtype=torch.float32)
+        pools.append(p)
+    return q, pools[0], pools[1]
+
+
+def layers_that_fit(w, device, want, reserve_gb=24):
+    free, _ = torch.cuda.mem_get_info(device)
+    per_layer = 2 * w.num_pool_blocks * w.block_bytes + (2 << 20)
+    fit = int((free - (reserve_gb << 30)) // per_layer)
+    return max(1, min(want, fit))
+
+
+def sample_to_host(w, tables, seqs, k_d, v_d):
+    """Compact sub-pool holding only the blocks of `seqs`, on the host, plus the
+    tables rewritten to it (torch indexing only)."""
+    used = w.used_blocks()
+    ids = np.concatenate([tables[s, :int(used[s])] for s in seqs]).astype(np.int64)
+    idx = torch.from_numpy(ids).to(k_d.device)
+    k = to_bits(k_d.index_select(0, idx))
+    v = to_bits(v_d.index_select(0, idx))
+    sub_tables = np.full((len(seqs), tables.shape[1]), -1, np.int32)
+    off = 0
+    for r, s in enumerate(seqs):
+        n = int(used[s])
+        sub_tables[r, :n] = np.arange(off, off + n, dtype=np.int32)
+        off += n
+    return k, v, sub_tables
+
+
+def checksum(pool, block_idx):
+    """Position-weighted 64-bit checksum of the listed blocks' bit patterns."""
+    x = pool.index_select(0, block_idx).view(torch.int16).reshape(len(block_idx), -1)
+    a = x.sum(dim=1, dtype=torch.int64)
+    wgt = torch.arange(1, len(block_idx) + 1, device=pool.device, dtype=torch.int64)
+    return int((a * wgt).sum().item()) ^ int(x[:, ::97].sum(dtype=torch.int64).item())
+
+
+def check_rows(got_rows, q_rows, k, v, tables, lens, scale, what):
+    ref = oracle.paged_decode_attn(q_rows, k, v, tables, lens, scale)
+    c = oracle.compare(got_rows, ref)
+    print(f"{what}: {c}", flush=True)
+    assert c["max_abs"] <= MAX_ABS and c["rel_l2"] <= REL_L2, (what, c)
+    assert c["worst_seq_rel_l2"] <= 2 * REL_L2, (what, c)
+
+
+def test_cfg4_full_depth_resident(device):
+    """64 layers x (K pool, V pool) resident at once (about 199 GB); one decode
+    step = 64 attention calls back to back.  Oracle: every request in 2 layers,
+    4 requests in every layer."""
+    w = wl.cfg4_phase_mixed()
+    assert_launchable(w)
+    n_layers = layers_that_fit(w, device, w.num_layers)
+    if n_layers < w.num_layers:
+        print(f"NOTE: only {n_layers} of {w.num_layers} layers fit in free HBM; running those", flush=True)
+    layers = [fill_layer(w, l, device) for l in range(n_layers)]
+    resident = sum(k.numel() * 2 + v.numel() * 2 for _, k, v in layers)
+    print(f"resident KV: {resident / 1e9:.1f} GB in {n_layers} layers", flush=True)
+    tables_d, lens_d = to_dev(w.block_tables), to_dev(w.context_lens)
+    shape = shape_of(w, max_context_len=int(w.context_lens.max()))
+    ws = torch.empty(pkv.pkv_attn_workspace_bytes(shape), dtype=torch.uint8, device=device)
+    outs = [torch.full(w.q_shape(), 0x7FC1, dtype=torch.int16, device=device) for _ in range(n_layers)]
+
+    def step():
+        for (q, k, v), out in zip(layers, outs):
+            pkv.paged_decode_attn(q, k, v, tables_d, lens_d, float(w.scale), out, shape, ws)
+
+    step()
+    torch.cuda.synchronize()
+    t0, t1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    t0.record()
+    step()
+    t1.record()
+    torch.cuda.synchronize()
+    ms = t0.elapsed_time(t1)
+    gbps = w.attn_algorithmic_bytes() * n_layers / (ms * 1e-3) / 1e9
+    print(f"full-depth step: {ms:.2f} ms for {n_layers} layers, {gbps:.0f} GB/s algorithmic", flush=True)
+
+    rng = np.random.default_rng(w.seed + 99)
+    full_layers = sorted(rng.choice(n_layers, size=min(2, n_layers), replace=False).tolist())
+    for l in full_layers:
+        q, k, v = layers[l]
+        check_rows(to_bits(outs[l]), to_bits(q), to_bits(k), to_bits(v), w.block_tables,
+                   w.context_lens, w.scale, f"cfg4 layer {l}, all requests")
+    seqs = sorted(rng.choice(w.num_seqs, size=4, replace=False).tolist())
+    for l in range(n_layers):
+        q, k_d, v_d = layers[l]
+        k, v, sub_tables = sample_to_host(w, w.block_tables, seqs, k_d, v_d)
+        check_rows(to_bits(outs[l])[seqs], to_bits(q)[seqs], k, v, sub_tables,
+                   w.context_lens[seqs], w.scale, f"cfg4 layer {l}, requests {seqs}")
+
+
+def test_cfg5_migration_next_to_decode(device):
+    """Per layer: gather the victims' K and V blocks into one reused staging buffer
+    and scatter them into reshuffled ids on stream A, while stream B runs decode
+    attention for the surviving 75 % of the batch.  Migrated blocks are bit-exact,
+    every other block untouched, the survivors' rows identical to a run without
+    migration, and attention after the move matches the oracle."""
+    n_layers = 6
+    w = wl.cfg4_phase_mixed(num_layers=n_layers)
+    mig = wl.make_migration(w, 0.25)
+    assert len(mig.victims) == 24 and len(mig.survivors) == 72
+    used = w.used_blocks()
+    surv_blocks = np.concatenate([w.block_tables[s, :int(used[s])] for s in mig.survivors])
+    # the two streams never touch the same block: that is what makes them race-free
+    assert len(np.intersect1d(surv_blocks, mig.old_ids)) == 0
+    assert len(np.intersect1d(surv_blocks, mig.new_ids)) == 0
+    assert len(np.unique(mig.new_ids)) == len(mig.new_ids)
+    assert mig.old_ids.max() < w.num_pool_blocks and mig.new_ids.max() < w.num_pool_blocks
+
+    n_layers = layers_that_fit(w, device, n_layers)
+    layers = [fill_layer(w, l, device) for l in range(n_layers)]
+    ws_surv = wl.subset(w, mig.survivors)
+    assert_launchable(ws_surv)
+    surv_idx = torch.from_numpy(mig.survivors.astype(np.int64)).to(device)
+    st_tables, st_lens = to_dev(ws_surv.block_tables), to_dev(ws_surv.context_lens)
+    old_d, new_d = to_dev(mig.old_ids), to_dev(mig.new_ids)
+    n = len(mig.old_ids)
+    staging = torch.empty((n,) + tuple(w.pool_shape()[1:]), dtype=torch.bfloat16, device=device)
+    touched = np.union1d(mig.old_ids, mig.new_ids)
+    untouched = torch.from_numpy(np.setdiff1d(np.arange(w.num_pool_blocks), touched)).to(device)
+
+    # reference for the survivors: the same call with nothing else running
+    q_surv = [q.index_select(0, surv_idx).contiguous() for q, _, _ in layers]
+    alone = [run_attn_dev(ws_surv, q_surv[l], layers[l][1], layers[l][2], st_tables, st_lens)
+             for l in range(n_layers)]
+    before = [(k.index_select(0, old_d.long()), v.index_select(0, old_d.long()),
+               checksum(k, untouched), checksum(v, untouched))
+              for _, k, v in layers]
+    torch.cuda.synchronize()
+
+    stream_a, stream_b = torch.cuda.Stream(device), torch.cuda.Stream(device)
+    shape_s = shape_of(ws_surv)
+    ws_b = torch.empty(pkv.pkv_attn_workspace_bytes(shape_s), dtype=torch.uint8, device=device)
+    together = [torch.full(ws_surv.q_shape(), 0x7FC1, dtype=torch.int16, device=device)
+                for _ in range(n_layers)]
+    bb, NB = w.block_bytes, w.num_pool_blocks
+    for l, (q, k, v) in enumerate(layers):
+        for pool in (k, v):
+            pkv.kv_blocks_gather(pool, old_d, staging, n, bb, NB, stream_a)
+            pkv.kv_blocks_scatter(staging, pool, new_d, n, bb, NB, stream_a)
+        pkv.paged_decode_attn(q_surv[l], k, v, st_tables, st_lens, float(w.scale), together[l],
+                              shape_s, ws_b, stream_b)
+    torch.cuda.synchronize()
+
+    for l, (q, k, v) in enumerate(layers):
+        k_old, v_old, k_sum, v_sum = before[l]
+        assert torch.equal(k.index_select(0, new_d.long()), k_old), f"layer {l}: K blocks differ"
+        assert torch.equal(v.index_select(0, new_d.long()), v_old), f"layer {l}: V blocks differ"
+        assert checksum(k, untouched) == k_sum and checksum(v, untouched) == v_sum, \
+            f"layer {l}: a block outside the migration changed"
+        assert torch.equal(together[l], alone[l]), f"layer {l}: survivors changed under migration"
+
+    # attention for the whole batch after the move, tables rewritten
+    w_after = wl.Workload("cfg5_after", w.num_q_heads, w.num_kv_heads, w.context_lens,
+                          mig.tables_after, w.num_pool_blocks, seed=w.seed)
+    assert_launchable(w_after)
+    rng = np.random.default_rng(w.seed + 7)
+    seqs = sorted(set(rng.choice(mig.victims, size=4, replace=False).tolist()
+                      + rng.choice(mig.survivors, size=2, replace=False).tolist()))
+    ta_d, la_d = to_dev(w_after.block_tables), to_dev(w_after.context_lens)
+    for l in (0, n_layers - 1):
+        q, k_d, v_d = layers[l]
+        out = run_attn_dev(w_after, q, k_d, v_d, ta_d, la_d)
+        torch.cuda.synchronize()
+        k, v, sub_tables = sample_to_host(w_after, mig.tables_after, seqs, k_d, v_d)
+        check_rows(to_bits(out)[seqs], to_bits(q)[seqs], k, v, sub_tables, w.context_lens[seqs],
+                   w.scale, f"cfg5 layer {l} after migration, requests {seqs}")
