@@ -37,7 +37,7 @@ extern "C" {
  * (continuous batching, paper Section II-B), so nothing here is fixed at
  * library start-up. */
 typedef struct {
-  int32_t num_seqs;           /* S: requests in this step's batch, 0..4096              */
+  int32_t num_seqs;           /* S: requests in this step's batch, 0..2048              */
   int32_t num_q_heads;        /* Hq                                                      */
   int32_t num_kv_heads;       /* Hkv; Hq % Hkv == 0; query heads h*G..h*G+G-1 share
                                  KV head h (G = Hq/Hkv, 1 <= G <= 16)                    */

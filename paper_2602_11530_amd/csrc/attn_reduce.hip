@@ -49,11 +49,17 @@ __global__ __launch_bounds__(kRowsPerGroup * 64) void attn_reduce_kernel(AttnLau
   const int last = gp0 + (nps - 1) + share_owner(pos_a + nb - 1, T, W);
   const int np = last - first + 1;   // records of this row, a neutral filler possibly among them
 
-  auto rec = [&](int p) -> int64_t { return (int64_t)(first + p) * a.G + g; };
+  const int rec_floats = record_floats(a.G);
+  auto stats = [&](int p) -> float2 {   // (max, sum) of record p for this head
+    return *(const float2*)(a.ws_rec + (int64_t)(first + p) * rec_floats + a.G * kHeadDim + 2 * g);
+  };
+  auto part_row = [&](int p) -> const float* {   // its un-normalised row
+    return a.ws_rec + (int64_t)(first + p) * rec_floats + g * kHeadDim;
+  };
   float M = kNegInf;
   for (int p0 = 0; p0 < np; p0 += 64) {
     const int p = p0 + lane;
-    if (p < np) M = fmaxf(M, a.ws_ml[rec(p)].x);
+    if (p < np) M = fmaxf(M, stats(p).x);
   }
   M = wave_max(M);
 
@@ -62,7 +68,7 @@ __global__ __launch_bounds__(kRowsPerGroup * 64) void attn_reduce_kernel(AttnLau
     const int p = p0 + lane;
     float w = 0.f;
     if (p < np) {
-      const float2 ml = a.ws_ml[rec(p)];
+      const float2 ml = stats(p);
       // A record whose blocks were all unmapped, or a filler, carries max = -inf, sum = 0.
       w = (ml.x == kNegInf) ? 0.f : __builtin_amdgcn_exp2f(ml.x - M);
       lsum = __builtin_fmaf(w, ml.y, lsum);
@@ -75,7 +81,7 @@ __global__ __launch_bounds__(kRowsPerGroup * 64) void attn_reduce_kernel(AttnLau
       for (int u = 0; u < kBatch; ++u) {
         const int j = min(j0 + u, cnt - 1);   // clamped rows get weight 0
         wj[u] = (j0 + u < cnt) ? __int_as_float(__builtin_amdgcn_readlane(__float_as_int(w), j)) : 0.f;
-        v[u] = *((const float2*)(a.ws_acc + rec(p0 + j) * kHeadDim) + lane);
+        v[u] = *((const float2*)part_row(p0 + j) + lane);
       }
 #pragma unroll
       for (int u = 0; u < kBatch; ++u) {

@@ -79,9 +79,6 @@ __device__ __forceinline__ void store_record16(float* p, f32x4 v) {
   // op may overwrite its data registers (the compiler cannot see that this is a store)
   asm volatile("global_store_dwordx4 %0, %1, off\n\ts_nop 1" : : "v"(p), "v"(v) : "memory");
 }
-__device__ __forceinline__ void store_record8(float2* p, f32x2 v) {
-  asm volatile("global_store_dwordx2 %0, %1, off\n\ts_nop 1" : : "v"(p), "v"(v) : "memory");
-}
 
 // One window of block descriptors: lane i describes stream index jbase + i.
 struct Window {
@@ -98,6 +95,10 @@ __global__ __launch_bounds__(kStreamWavesPerGroup * 64) void attn_stream_kernel(
   int* cumB = smem;                  // [S+1] blocks before request s
   int* cumNP = smem + (a.S + 1);     // [S+1] partitions before request s
   int* lens = smem + 2 * (a.S + 1);  // [S]   clamped context lengths
+  // then room for rec_buffered finished records per wavefront, 16-byte aligned
+  const int rec_floats = record_floats(a.G);
+  float* rec_stage = (float*)(smem + ((3 * (a.S + 1) + 3) & ~3)) +
+                     (threadIdx.x >> 6) * a.rec_buffered * rec_floats;
 
   const int wave = threadIdx.x >> 6;
   const int lane = threadIdx.x & 63;
@@ -186,7 +187,8 @@ __global__ __launch_bounds__(kStreamWavesPerGroup * 64) void attn_stream_kernel(
     const int kvh0 = (qrow0 - s0 * a.Hq) / G;
     const int b0 = (pos0 - Hkv * cumB[s0]) - kvh0 * (cumB[s0 + 1] - cumB[s0]);
     if (w > 0 && b0 > 0 && b0 % bpp == 0 && lane < G)
-      a.ws_ml[(int64_t)(slot0 - 1) * G + lane] = make_float2(kNegInf, 0.f);
+      *(float2*)(a.ws_rec + (int64_t)(slot0 - 1) * rec_floats + G * kHeadDim + 2 * lane) =
+          make_float2(kNegInf, 0.f);
   }
 
   const int64_t head_elems = (int64_t)kBlockTokens * kHeadDim;  // one (block, KV head) slab
@@ -217,6 +219,24 @@ __global__ __launch_bounds__(kStreamWavesPerGroup * 64) void attn_stream_kernel(
     for (int jj = 0; jj < 4; ++jj) k[jj] = kp[4 * jj];
 #pragma unroll
     for (int jj = 0; jj < 4; ++jj) v[jj] = vp[64 * jj];
+  };
+
+  // Finished records wait in LDS and go out several at a time, with full-width
+  // stores, and the rest when the share is done.  A store in the middle of the
+  // stream is expensive out of proportion to its size: loads and stores retire
+  // through one counter, so the KV loads issued after it cannot be consumed
+  // before it has been acknowledged, and that costs one stall of several
+  // microseconds per burst of stores however few bytes it carries.
+  int nrec = 0;        // records parked in LDS
+  int rec_slots = 0;   // lane r: slot of parked record r
+  auto drain_records = [&]() {
+    for (int r = 0; r < nrec; ++r) {
+      const int slot = __builtin_amdgcn_readlane(rec_slots, r);
+      float* dst = a.ws_rec + (int64_t)slot * rec_floats;
+      const float* src = rec_stage + r * rec_floats;
+      for (int f = 4 * lane; f < rec_floats; f += 256) store_record16(dst + f, *(const f32x4*)(src + f));
+    }
+    nrec = 0;
   };
 
   auto consume = [&](u32x4 (&k)[4], u32x4 (&v)[4], int j) {
@@ -305,16 +325,20 @@ __global__ __launch_bounds__(kStreamWavesPerGroup * 64) void attn_stream_kernel(
       const int slot = __builtin_amdgcn_readlane(dA.slot, idx);
       float lt = l + __shfl_xor(l, 16);
       lt += __shfl_xor(lt, 32);
+      // The record is assembled in LDS in its memory order and parked there.
+      float* rec = rec_stage + nrec * rec_floats;
 #pragma unroll
       for (int r = 0; r < 4; ++r) {
         const int h = 4 * c + r;
         if (h < G) {
-          float* dst = a.ws_acc + ((int64_t)slot * G + h) * kHeadDim + 8 * n;
-          store_record16(dst, f32x4{o[0][r], o[1][r], o[2][r], o[3][r]});
-          store_record16(dst + 4, f32x4{o[4][r], o[5][r], o[6][r], o[7][r]});
+          f32x4* row = (f32x4*)(rec + h * kHeadDim + 8 * n);
+          row[0] = f32x4{o[0][r], o[1][r], o[2][r], o[3][r]};
+          row[1] = f32x4{o[4][r], o[5][r], o[6][r], o[7][r]};
         }
       }
-      if (c == 0 && n < G) store_record8(a.ws_ml + (int64_t)slot * G + n, f32x2{m, lt});
+      if (c == 0) *(f32x2*)(rec + G * kHeadDim + 2 * n) = (n < G) ? f32x2{m, lt} : f32x2{kNegInf, 0.f};
+      rec_slots = (lane == nrec) ? slot : rec_slots;
+      if (++nrec == a.rec_buffered) drain_records();
       m = kNegInf;
       l = 0.f;
 #pragma unroll
@@ -342,12 +366,22 @@ __global__ __launch_bounds__(kStreamWavesPerGroup * 64) void attn_stream_kernel(
       dB = describe(jbase + kWindow);
     }
   }
+  drain_records();
 }
 
 }  // namespace
 
-hipError_t launch_attn_stream(const AttnLaunch& a, hipStream_t stream) {
-  const size_t lds = (size_t)(3 * (a.S + 1)) * sizeof(int);
+hipError_t launch_attn_stream(const AttnLaunch& a_in, hipStream_t stream) {
+  AttnLaunch a = a_in;
+  // LDS per workgroup: the prefix arrays, then as many parked records per
+  // wavefront as fit in 64 KiB (at most 8).
+  const size_t cum_bytes = (size_t)((3 * (a.S + 1) + 3) & ~3) * sizeof(int);
+  const size_t rec_bytes = (size_t)record_floats(a.G) * sizeof(float);
+  const size_t room = (size_t)64 * 1024 - cum_bytes;
+  a.rec_buffered = (int)(room / (kStreamWavesPerGroup * rec_bytes));
+  if (a.rec_buffered > 8) a.rec_buffered = 8;
+  if (a.rec_buffered < 1) return hipErrorInvalidValue;
+  const size_t lds = cum_bytes + (size_t)kStreamWavesPerGroup * a.rec_buffered * rec_bytes;
   hipLaunchKernelGGL(attn_stream_kernel, dim3(kStreamGroups), dim3(kStreamWavesPerGroup * 64), lds,
                      stream, a);
   return hipGetLastError();

@@ -49,21 +49,19 @@ int check_shape(const pkv_attn_shape* sh, Geometry* g) {
   g->P = P;
   g->max_ctx = max_ctx;
   g->slots = (int64_t)sh->num_kv_heads * sh->num_seqs * NP + pkv::kStreamWaves + 1;
-  if (g->slots * G > INT32_MAX) return PKV_ERR_SHAPE;
+  if (g->slots > INT32_MAX) return PKV_ERR_SHAPE;
   return PKV_OK;
 }
 
-// Workspace: partial rows, their (max, sum) pairs, the two prefix arrays.
+// Workspace: the partial records, then the two prefix arrays.
 struct WorkspaceLayout {
-  size_t acc_bytes, ml_bytes, cum_bytes;
-  size_t total() const { return acc_bytes + ml_bytes + cum_bytes; }
+  size_t rec_bytes, cum_bytes;
+  size_t total() const { return rec_bytes + cum_bytes; }
 };
 
 WorkspaceLayout workspace_layout(const pkv_attn_shape* sh, const Geometry& g) {
   WorkspaceLayout w;
-  const size_t rows = (size_t)g.slots * g.G;
-  w.acc_bytes = rows * pkv::kHeadDim * sizeof(float);
-  w.ml_bytes = (rows * sizeof(float2) + 15) & ~(size_t)15;
+  w.rec_bytes = (size_t)g.slots * pkv::record_floats(g.G) * sizeof(float);
   w.cum_bytes = ((size_t)2 * (sh->num_seqs + 1) * sizeof(int32_t) + 15) & ~(size_t)15;
   return w;
 }
@@ -149,9 +147,8 @@ int paged_decode_attn(const void* q, const void* k_pool, const void* v_pool,
   a.scale_log2e = scale * 1.4426950408889634f;
   const WorkspaceLayout lay = workspace_layout(shape, g);
   char* ws = static_cast<char*>(workspace);
-  a.ws_acc = reinterpret_cast<float*>(ws);
-  a.ws_ml = reinterpret_cast<float2*>(ws + lay.acc_bytes);
-  a.ws_cum = reinterpret_cast<int32_t*>(ws + lay.acc_bytes + lay.ml_bytes);
+  a.ws_rec = reinterpret_cast<float*>(ws);
+  a.ws_cum = reinterpret_cast<int32_t*>(ws + lay.rec_bytes);
 
   hipStream_t st = static_cast<hipStream_t>(stream);
   hipError_t e = pkv::launch_attn_stream(a, st);

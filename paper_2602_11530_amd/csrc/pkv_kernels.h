@@ -13,7 +13,7 @@ constexpr int kHeadDim = 128;        // D
 constexpr int kBlockTokens = 16;     // B
 constexpr int kMaxPartition = 65536; // tokens covered by one partial result, upper bound
 constexpr int kMaxGroup = 16;        // query heads per KV head
-constexpr int kMaxSeqs = 4096;       // per-request prefix arrays live in LDS
+constexpr int kMaxSeqs = 2048;       // per-request prefix arrays live in LDS
 
 // The attention pass is a persistent launch sized for the 256 compute units of
 // an MI355X: two 4-wave workgroups per unit, each wavefront streaming an equal
@@ -43,6 +43,10 @@ __host__ __device__ inline int share_owner(int64_t pos, int64_t T, int64_t W) {
   return (int)(((pos + 1) * W - 1) / T);
 }
 
+// One partial record: G un-normalised rows of D floats, then (reference max in
+// log2 units, partial sum) for up to kMaxGroup heads.  Rows are 16-byte multiples.
+__host__ __device__ inline int record_floats(int G) { return G * kHeadDim + 2 * kMaxGroup; }
+
 struct AttnLaunch {
   const uint16_t* q;
   const uint16_t* k_pool;
@@ -50,14 +54,14 @@ struct AttnLaunch {
   const int32_t* block_tables;
   const int32_t* context_lens;
   uint16_t* out;
-  float* ws_acc;   // [slots * G][D]  un-normalised partial outputs
-  float2* ws_ml;   // [slots * G]     (reference max in log2 units, partial sum)
+  float* ws_rec;   // [slots][record_floats(G)] partial records, see record_floats()
   int32_t* ws_cum; // [2 * (S + 1)]   cumB then cumNP, written by the stream pass for the merge
   float scale_log2e;
   int S, Hq, Hkv, G, MAXB;
   int P;           // partition size, tokens
   int max_ctx;     // context lengths are clamped to [0, max_ctx] (<= MAXB * 16)
   int NB;          // physical blocks per pool; ids outside [0, NB) are never followed
+  int rec_buffered; // finished records a wavefront keeps in LDS before writing them out (>= 1)
 };
 
 // Stream pass: kStreamWaves persistent wavefronts, each writing its runs' partial records.

@@ -41,12 +41,12 @@ def test_partition_and_workspace():
     sh = pkv.make_shape(128, 40, 8, 2048, 70000, partition_size=512)
     assert pkv.pkv_attn_partition_size(sh) == 512
     a16 = lambda x: (x + 15) // 16 * 16
+    rec = (5 * 128 + 32) * 4             # one record: 5 rows of 128 floats + 16 (max, sum) pairs
     slots = 8 * 128 * 64 + 2048 + 1      # kv heads x requests x partitions + stream wavefronts + 1
-    rows = slots * 5
-    assert pkv.pkv_attn_workspace_bytes(sh) == rows * 128 * 4 + a16(rows * 8) + a16(2 * 129 * 4)
+    assert pkv.pkv_attn_workspace_bytes(sh) == slots * rec + a16(2 * 129 * 4)
     sh.max_context_len = 512
     slots = 8 * 128 * 1 + 2048 + 1
-    assert pkv.pkv_attn_workspace_bytes(sh) == slots * 5 * 512 + a16(slots * 5 * 8) + a16(2 * 129 * 4)
+    assert pkv.pkv_attn_workspace_bytes(sh) == slots * rec + a16(2 * 129 * 4)
     sh = pkv.make_shape(4, 8, 2, 19, 128)
     P = pkv.pkv_attn_partition_size(sh)
     assert P % 16 == 0 and 16 <= P <= 65536
@@ -55,7 +55,7 @@ def test_partition_and_workspace():
 
 @pytest.mark.parametrize("kw", [
     dict(head_dim=64), dict(block_size=32), dict(num_q_heads=9), dict(num_kv_heads=0),
-    dict(partition_size=24), dict(partition_size=65536 + 16), dict(num_seqs=4097), dict(partition_size=-16),
+    dict(partition_size=24), dict(partition_size=65536 + 16), dict(num_seqs=2049), dict(partition_size=-16),
     dict(max_blocks_per_seq=0), dict(num_seqs=-1), dict(max_context_len=20 * 16),
     dict(max_context_len=-1), dict(num_pool_blocks=0), dict(num_pool_blocks=2 ** 31),
 ])
