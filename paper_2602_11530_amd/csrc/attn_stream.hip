@@ -173,7 +173,7 @@ __global__ __launch_bounds__(kStreamWavesPerGroup * 64) void attn_stream_kernel(
   };
 
   Window dA = describe(0);
-  Window dB = describe(kWindow);
+  Window dB = dA;   // described after the first KV loads are on their way (below)
   int jbase = 0;
 
   // When this share begins exactly on a partition boundary the previous
@@ -351,6 +351,7 @@ __global__ __launch_bounds__(kStreamWavesPerGroup * 64) void attn_stream_kernel(
   u32x4 kbuf[kRing][4], vbuf[kRing][4];
 #pragma unroll
   for (int i = 0; i < kRing - 1; ++i) issue(kbuf[i], vbuf[i], i);
+  dB = describe(kWindow);
   for (int j = 0; j < nshare; j += kRing) {
 #pragma unroll
     for (int i = 0; i < kRing; ++i) {
