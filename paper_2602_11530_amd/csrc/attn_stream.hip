@@ -40,6 +40,14 @@
 namespace pkv {
 namespace {
 
+#ifndef PKV_KV_NT
+#define PKV_KV_NT 1
+#endif
+#if PKV_KV_NT
+#define PKV_KV_LOAD(p) __builtin_nontemporal_load(p)
+#else
+#define PKV_KV_LOAD(p) (*(p))
+#endif
 #ifndef PKV_RING
 #define PKV_RING 4
 #endif
@@ -216,9 +224,9 @@ __global__ __launch_bounds__(kStreamWavesPerGroup * 64) void attn_stream_kernel(
     const u32x4* kp = (const u32x4*)(a.k_pool + base) + koff;
     const u32x4* vp = (const u32x4*)(a.v_pool + base) + lane;
 #pragma unroll
-    for (int jj = 0; jj < 4; ++jj) k[jj] = kp[4 * jj];
+    for (int jj = 0; jj < 4; ++jj) k[jj] = PKV_KV_LOAD(kp + 4 * jj);
 #pragma unroll
-    for (int jj = 0; jj < 4; ++jj) v[jj] = vp[64 * jj];
+    for (int jj = 0; jj < 4; ++jj) v[jj] = PKV_KV_LOAD(vp + 64 * jj);
   };
 
   // Finished records wait in LDS and go out several at a time, with full-width
