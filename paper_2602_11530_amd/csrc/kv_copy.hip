@@ -7,27 +7,13 @@
 namespace pkv {
 namespace {
 
-#ifndef PKV_COPY_NT
-#define PKV_COPY_NT 3
-#endif
-#if PKV_COPY_NT & 1
-#define PKV_COPY_LOAD(p) __builtin_nontemporal_load(p)
-#else
-#define PKV_COPY_LOAD(p) (*(p))
-#endif
-#if PKV_COPY_NT & 2
-#define PKV_COPY_STORE(v, p) __builtin_nontemporal_store(v, p)
-#else
-#define PKV_COPY_STORE(v, p) (*(p) = (v))
-#endif
-#ifndef PKV_COPY_THREADS
-#define PKV_COPY_THREADS 256
-#endif
-#ifndef PKV_COPY_CHUNKS
-#define PKV_COPY_CHUNKS 8
-#endif
-constexpr int kCopyThreads = PKV_COPY_THREADS;
-constexpr int kChunksPerThread = PKV_COPY_CHUNKS;                               // 16-byte chunks
+// Loads and stores are nontemporal.  Neither side is reused soon enough to be
+// worth a cache line, and in a decode loop the choice matters more for the next
+// kernel than for this one: with ordinary or write-through (sc1) stores the copy
+// itself gets up to 20 % faster but the attention call that follows slows by
+// 17-30 % while the lines drain; nontemporal stores are the best total.
+constexpr int kCopyThreads = 256;
+constexpr int kChunksPerThread = 8;                               // 16-byte chunks
 constexpr int kChunksPerGroup = kCopyThreads * kChunksPerThread;  // 32 KiB per workgroup
 
 // blockIdx.x = index into block_ids, blockIdx.y = 32 KiB slice of that block.
@@ -50,14 +36,14 @@ __global__ __launch_bounds__(kCopyThreads) void kv_block_copy_kernel(
     // issued before the first store, with no per-lane guard in the way.
     u32x4 v[kChunksPerThread];
 #pragma unroll
-    for (int u = 0; u < kChunksPerThread; ++u) v[u] = PKV_COPY_LOAD(s + c0 + (int64_t)u * kCopyThreads);
+    for (int u = 0; u < kChunksPerThread; ++u) v[u] = __builtin_nontemporal_load(s + c0 + (int64_t)u * kCopyThreads);
 #pragma unroll
-    for (int u = 0; u < kChunksPerThread; ++u) PKV_COPY_STORE(v[u], d + c0 + (int64_t)u * kCopyThreads);
+    for (int u = 0; u < kChunksPerThread; ++u) __builtin_nontemporal_store(v[u], d + c0 + (int64_t)u * kCopyThreads);
   } else {
     // Ragged last slice of an odd block size.
     for (int u = 0; u < kChunksPerThread; ++u) {
       const int64_t c = c0 + (int64_t)u * kCopyThreads;
-      if (c < chunks_per_block) PKV_COPY_STORE(PKV_COPY_LOAD(s + c), d + c);
+      if (c < chunks_per_block) __builtin_nontemporal_store(__builtin_nontemporal_load(s + c), d + c);
     }
   }
 }
