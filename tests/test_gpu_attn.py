@@ -213,3 +213,53 @@ def test_corrupt_table_entries_are_not_followed(device):
     ref = oracle.paged_decode_attn(q[:2], k, v, keep.block_tables, keep.context_lens, w.scale)
     c = oracle.compare(got[:2], ref)
     assert c["max_abs"] <= MAX_ABS and c["rel_l2"] <= REL_L2, c
+
+
+def test_bench_launch_configuration(device):
+    """Config 2 exactly as bench.py launches it: library-chosen partitioning and
+    the batch's true maximum length as the host bound."""
+    w = wl.cfg2_qwen32b()
+    q_d, k_d, v_d = device_tensors(w)
+    out = run_attn_dev(w, q_d, k_d, v_d, to_dev(w.block_tables), to_dev(w.context_lens),
+                       partition_size=0, max_context_len=int(w.context_lens.max()))
+    torch.cuda.synchronize()
+    check(w, to_bits(q_d), to_bits(k_d), to_bits(v_d), to_bits(out), "bench configuration")
+
+
+def _random_case(rng, case):
+    hkv = int(rng.choice([1, 2, 4, 8]))
+    g = int(rng.choice([1, 2, 4, 5, 7, 8, 16]))
+    kind = case % 6
+    if kind == 0:      # a handful of blocks: fewer blocks than persistent wavefronts
+        lens = rng.integers(0, 40, size=int(rng.integers(1, 6)))
+    elif kind == 1:    # many short requests, some empty
+        lens = rng.integers(0, 100, size=int(rng.integers(50, 300)))
+        lens[rng.random(len(lens)) < 0.2] = 0
+    elif kind == 2:    # block count right around the number of wavefronts
+        n = max(1, 2048 // hkv)
+        lens = np.full(int(rng.integers(1, 4)), 16 * (n // 2), dtype=np.int64)
+        lens[0] += int(rng.integers(-40, 40))
+    elif kind == 3:    # lengths on exact partition multiples: shares start on partition cuts
+        lens = 512 * rng.integers(1, 9, size=int(rng.integers(2, 20)))
+    elif kind == 4:    # one long request among short ones
+        lens = np.concatenate([rng.integers(1, 64, size=20), [int(rng.integers(5000, 20000))]])
+    else:              # mixed
+        lens = rng.integers(1, 3000, size=int(rng.integers(1, 40)))
+    P = int(rng.choice([0, 16, 32, 64, 256, 512, 1024, 2048]))
+    return np.maximum(np.asarray(lens, dtype=np.int64), 0), hkv * g, hkv, P
+
+
+@pytest.mark.parametrize("case", range(36))
+def test_random_shapes(device, case):
+    """Seeded random batches aimed at the corners of the stream decomposition:
+    fewer blocks than wavefronts, shares that begin on partition boundaries, empty
+    requests, every group size."""
+    rng = np.random.default_rng(9000 + case)
+    lens, hq, hkv, P = _random_case(rng, case)
+    w = wl.custom(lens, hq, hkv, seed=500 + case, partition_size=P,
+                  num_pool_blocks=int(((lens + 15) // 16).sum()) + int(rng.integers(1, 50)))
+    q, k, v = wl.make_host_tensors(w, poison_unused=True)
+    got = run_attn(w, q, k, v)
+    check(w, q, k, v, got, f"case {case}: S={len(lens)} hq={hq} hkv={hkv} P={P} tokens={int(lens.sum())}")
+    for s in np.nonzero(lens == 0)[0]:
+        assert not got.reshape(w.q_shape())[s].any()
