@@ -138,6 +138,30 @@ int kv_blocks_scatter(const void* staging, void* pool, const int32_t* block_ids,
                       int64_t n_blocks, int64_t block_bytes, int64_t num_pool_blocks,
                       void* stream);
 
+/*
+ * Writes the newly generated token's K and V rows into their slots: the step
+ * that precedes attention in every decode iteration ("incrementally updating
+ * [the KV caches] with each newly generated token", paper Section II-A).
+ * context_lens[s] already counts the new token, so its row goes to position
+ * t = context_lens[s] - 1:
+ *
+ *   k_pool[ block_tables[s][t / B] ][kvh][t % B][:] = k_new[s][kvh][:]   (V alike)
+ *
+ * for every request with context_lens[s] >= 1 (after clamping to
+ * max_context_len) and every KV head.  A request with context_lens[s] <= 0, or
+ * whose table entry lies outside [0, num_pool_blocks), is skipped.  Nothing else
+ * in the pools is written; the copy is bit-exact.
+ *
+ *   k_new, v_new  device  bf16 [S][Hkv][D]
+ *   k_pool,v_pool device  bf16 [NB][Hkv][B][D]
+ *   block_tables  device  int32 [S][MAXB]
+ *   context_lens  device  int32 [S]
+ *   shape         host    (num_q_heads and partition_size are not used)
+ */
+int kv_append(const void* k_new, const void* v_new, void* k_pool, void* v_pool,
+              const int32_t* block_tables, const int32_t* context_lens,
+              const pkv_attn_shape* shape, void* stream);
+
 /* Static text for a status code. */
 const char* pkv_status_string(int status);
 

@@ -47,6 +47,8 @@ def _load() -> ctypes.CDLL:
         lib.pkv_oracle_kv_blocks_scatter.argtypes = [p, p, p, i64, i64, i64]
         lib.pkv_oracle_kv_blocks_scatter.restype = ctypes.c_int
         lib.pkv_oracle_max_threads.restype = ctypes.c_int
+        lib.pkv_oracle_kv_append.argtypes = [p, p, p, p, p, p, i64, i64, i64, i64, i64, i64]
+        lib.pkv_oracle_kv_append.restype = ctypes.c_int
         _lib = lib
     return _lib
 
@@ -121,6 +123,25 @@ def kv_blocks_scatter(staging: np.ndarray, pool: np.ndarray, block_ids) -> np.nd
     if rc != 0:
         raise ValueError(f"oracle rejected its input (code {rc})")
     return out
+
+
+def kv_append(k_new, v_new, k_pool, v_pool, block_tables, context_lens):
+    """Copies of the pools with every request's newest K,V row at position L_s - 1."""
+    k_new, v_new = _c(k_new, np.uint16), _c(v_new, np.uint16)
+    k_out = np.array(_c(k_pool, np.uint16), copy=True, order="C")
+    v_out = np.array(_c(v_pool, np.uint16), copy=True, order="C")
+    block_tables, context_lens = _c(block_tables, np.int32), _c(context_lens, np.int32)
+    S, Hkv, D = k_new.shape
+    NB, Hkv2, B, D2 = k_out.shape
+    if (Hkv2, D2) != (Hkv, D) or v_new.shape != k_new.shape or v_out.shape != k_out.shape:
+        raise ValueError("inconsistent shapes")
+    rc = _load().pkv_oracle_kv_append(k_new.ctypes.data, v_new.ctypes.data, k_out.ctypes.data,
+                                      v_out.ctypes.data, block_tables.ctypes.data,
+                                      context_lens.ctypes.data, S, Hkv, D, B,
+                                      block_tables.shape[1], NB)
+    if rc != 0:
+        raise ValueError(f"oracle rejected its input (code {rc})")
+    return k_out, v_out
 
 
 def timed_attn(q, k_pool, v_pool, block_tables, context_lens, scale, threads: int = 0):

@@ -28,6 +28,10 @@
  *     gather : staging[i] = pool[ids[i]]     scatter : pool[ids[i]] = staging[i]
  *   bytewise, everything else untouched.
  *
+ *   Before attention the decode step stores the new token's K and V rows at
+ *   position L_s - 1 of each request's cache (Section II-A: the cache is updated
+ *   with each newly generated token); pinned by numpy indexing.
+ *
  * Pool layout: [NB, Hkv, B, D] row-major for K and for V.
  *
  * Parity pins (tests, CPU only): dense brute force written in numpy on tiny
@@ -141,5 +145,30 @@ int pkv_oracle_kv_blocks_scatter(const uint8_t* staging, uint8_t* pool, const in
   free(seen);
   for (int64_t i = 0; i < n; ++i)
     memcpy(pool + (int64_t)ids[i] * block_bytes, staging + i * block_bytes, (size_t)block_bytes);
+  return 0;
+}
+
+/* The new token's K and V rows of every request go to position L_s - 1 of its
+ * paged cache (the cache is updated with each generated token, Section II-A;
+ * L_s already counts that token).  Requests with L_s <= 0 are skipped. */
+int pkv_oracle_kv_append(const uint16_t* k_new, const uint16_t* v_new, uint16_t* k_pool,
+                         uint16_t* v_pool, const int32_t* block_tables,
+                         const int32_t* context_lens, int64_t S, int64_t Hkv, int64_t D, int64_t B,
+                         int64_t MAXB, int64_t NB) {
+  for (int64_t s = 0; s < S; ++s) {
+    const int64_t L = context_lens[s];
+    if (L <= 0) continue;
+    const int64_t t = L - 1;
+    if (t / B >= MAXB) return -1;
+    const int64_t pb = block_tables[s * MAXB + t / B];
+    if (pb < 0 || pb >= NB) return -2;
+    for (int64_t h = 0; h < Hkv; ++h) {
+      const int64_t dst = ((pb * Hkv + h) * B + t % B) * D;
+      for (int64_t d = 0; d < D; ++d) {
+        k_pool[dst + d] = k_new[(s * Hkv + h) * D + d];
+        v_pool[dst + d] = v_new[(s * Hkv + h) * D + d];
+      }
+    }
+  }
   return 0;
 }

@@ -23,7 +23,7 @@ PKV_ERR_LAUNCH = -5
 
 EXPORTS = (
     "pkv_attn_partition_size", "pkv_attn_workspace_bytes", "paged_decode_attn",
-    "kv_blocks_gather", "kv_blocks_scatter", "pkv_status_string",
+    "kv_blocks_gather", "kv_blocks_scatter", "kv_append", "pkv_status_string",
     "pkv_last_launch_error", "pkv_version",
 )
 
@@ -82,6 +82,8 @@ def lib() -> ctypes.CDLL:
         L.kv_blocks_gather.restype = ctypes.c_int
         L.kv_blocks_scatter.argtypes = [vp, vp, i32p, i64, i64, i64, vp]
         L.kv_blocks_scatter.restype = ctypes.c_int
+        L.kv_append.argtypes = [vp, vp, vp, vp, i32p, i32p, shp, vp]
+        L.kv_append.restype = ctypes.c_int
         _lib = L
     return _lib
 
@@ -150,3 +152,11 @@ def kv_blocks_scatter(staging, pool, block_ids, n_blocks: int, block_bytes: int,
                       num_pool_blocks: int, stream=None) -> None:
     _check(lib().kv_blocks_scatter(_ptr(staging), _ptr(pool), _ptr(block_ids), n_blocks,
                                    block_bytes, num_pool_blocks, _stream(stream)))
+
+
+def kv_append(k_new, v_new, k_pool, v_pool, block_tables, context_lens, shape: AttnShape,
+              stream=None) -> None:
+    """Write each request's newest K and V rows into slot context_lens[s] - 1."""
+    _check(lib().kv_append(_ptr(k_new), _ptr(v_new), _ptr(k_pool), _ptr(v_pool),
+                           _ptr(block_tables), _ptr(context_lens), ctypes.byref(shape),
+                           _stream(stream)))

@@ -158,6 +158,25 @@ int paged_decode_attn(const void* q, const void* k_pool, const void* v_pool,
   return PKV_OK;
 }
 
+int kv_append(const void* k_new, const void* v_new, void* k_pool, void* v_pool,
+              const int32_t* block_tables, const int32_t* context_lens,
+              const pkv_attn_shape* shape, void* stream) {
+  Geometry g;
+  const int rc = check_shape(shape, &g);
+  if (rc != PKV_OK) return rc;
+  if (shape->num_seqs == 0) return PKV_OK;
+  if (!k_new || !v_new || !k_pool || !v_pool || !block_tables || !context_lens) return PKV_ERR_NULL;
+  if (misaligned16(k_new) || misaligned16(v_new) || misaligned16(k_pool) || misaligned16(v_pool) ||
+      (reinterpret_cast<uintptr_t>(block_tables) & 3u) || (reinterpret_cast<uintptr_t>(context_lens) & 3u))
+    return PKV_ERR_ALIGN;
+  const hipError_t e = pkv::launch_kv_append(
+      static_cast<const uint16_t*>(k_new), static_cast<const uint16_t*>(v_new),
+      static_cast<uint16_t*>(k_pool), static_cast<uint16_t*>(v_pool), block_tables, context_lens,
+      shape->num_seqs, shape->num_kv_heads, shape->max_blocks_per_seq, g.max_ctx,
+      (int)shape->num_pool_blocks, static_cast<hipStream_t>(stream));
+  return launch_status(e);
+}
+
 static int copy_call(const void* pool, const void* staging, const int32_t* block_ids,
                      int64_t n_blocks, int64_t block_bytes, int64_t num_pool_blocks, bool gather,
                      void* stream) {

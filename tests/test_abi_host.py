@@ -106,3 +106,18 @@ def test_copy_argument_errors_before_launch():
         assert fn(*args(16, 16, None), 4, 32768, 64, None) == pkv.PKV_ERR_NULL
         assert fn(*args(24, 16, 16), 4, 32768, 64, None) == pkv.PKV_ERR_ALIGN
         assert fn(*args(16, 18, 16), 4, 32768, 64, None) == pkv.PKV_ERR_ALIGN
+
+
+def test_append_argument_errors_before_launch():
+    L = pkv.lib()
+    sh = pkv.make_shape(4, 8, 2, 19, 128)
+    call = lambda *a: L.kv_append(*a)
+    assert call(None, 16, 16, 16, 16, 16, ctypes.byref(sh), None) == pkv.PKV_ERR_NULL
+    assert call(16, 16, 16, None, 16, 16, ctypes.byref(sh), None) == pkv.PKV_ERR_NULL
+    assert call(16, 16, 16, 16, 16, 16, None, None) == pkv.PKV_ERR_NULL
+    assert call(16, 24, 16, 16, 16, 16, ctypes.byref(sh), None) == pkv.PKV_ERR_ALIGN
+    assert call(16, 16, 16, 16, 18, 16, ctypes.byref(sh), None) == pkv.PKV_ERR_ALIGN
+    bad = pkv.make_shape(4, 8, 3, 19, 128)
+    assert call(16, 16, 16, 16, 16, 16, ctypes.byref(bad), None) == pkv.PKV_ERR_SHAPE
+    sh0 = pkv.make_shape(0, 8, 2, 19, 128)
+    assert call(None, None, None, None, None, None, ctypes.byref(sh0), None) == pkv.PKV_OK

@@ -263,3 +263,30 @@ def test_migration_round_trip_keeps_attention():
     v2 = oracle.kv_blocks_scatter(oracle.kv_blocks_gather(v, mig.old_ids), v, mig.new_ids)
     ref2 = oracle.paged_decode_attn(q, k2, v2, mig.tables_after, w.context_lens, w.scale)
     assert np.array_equal(ref, ref2)
+
+
+def test_kv_append_against_indexing():
+    w = wl.custom([1, 16, 17, 0, 300, 33], 8, 2, seed=31, num_pool_blocks=60)
+    rng = np.random.default_rng(6)
+    _, k, v = wl.make_host_tensors(w)
+    k_new = rng.integers(0, 65536, size=(w.num_seqs, 2, 128)).astype(np.uint16)
+    v_new = rng.integers(0, 65536, size=(w.num_seqs, 2, 128)).astype(np.uint16)
+    k2, v2 = oracle.kv_append(k_new, v_new, k, v, w.block_tables, w.context_lens)
+    wk, wv = k.copy(), v.copy()
+    for s, L in enumerate(w.context_lens):
+        if L > 0:
+            pb = w.block_tables[s, (L - 1) // 16]
+            wk[pb, :, (L - 1) % 16, :] = k_new[s]
+            wv[pb, :, (L - 1) % 16, :] = v_new[s]
+    assert np.array_equal(k2, wk) and np.array_equal(v2, wv)
+    assert (k2 != k).any() and np.array_equal(k, wl.make_host_tensors(w)[1])   # input not modified
+    # the appended row is the one attention sees last: with a huge score on it the output is its V row
+    q = np.zeros(w.q_shape(), np.uint16)
+    q[:] = wl.f32_to_bf16_bits(np.full(1, 8.0, np.float32))[0]
+    k_hot = np.full_like(k_new, wl.f32_to_bf16_bits(np.full(1, 8.0, np.float32))[0])
+    v_new = wl.normal_bf16(rng, v_new.shape)
+    k3, v3 = oracle.kv_append(k_hot, v_new, np.zeros_like(k), v, w.block_tables, w.context_lens)
+    ref = oracle.paged_decode_attn(q, k3, v3, w.block_tables, w.context_lens, 1.0)
+    for s, L in enumerate(w.context_lens):
+        if L > 0:
+            assert np.abs(ref[s, 0] - wl.bf16_bits_to_f64(v_new[s, 0])).max() < 1e-6
