@@ -35,6 +35,12 @@
 // lane ("descriptors"), one window ahead of use; the streaming loop itself only
 // reads a lane of those registers per block, so no memory access sits on the
 // address path of the KV loads.
+//
+// Memory traffic.  The eight 16-byte KV loads of a block are nontemporal and
+// unconditional; a ring of kRing register buffers keeps kRing - 1 blocks in
+// flight per wavefront.  Finished records are parked in LDS and written in
+// bursts of full-width write-through stores that the compiler's wait-count
+// bookkeeping does not see (see store_record16).
 #include "pkv_kernels.h"
 
 namespace pkv {
