@@ -109,6 +109,27 @@ int paged_decode_attn(const void* q, const void* k_pool, const void* v_pool,
                       size_t workspace_bytes, void* stream);
 
 /*
+ * The same attention for num_layers layers in one call.  A request has the same
+ * context length and the same block ids in every layer of the model, so one
+ * block table and one length array serve all layers while each layer has its
+ * own q, K pool, V pool and output (the decode iteration of paper Section II-A
+ * runs the attention of every layer over that layer's KV cache).  Equivalent to
+ * calling paged_decode_attn for l = 0 .. num_layers-1 in order on `stream`
+ * with the one workspace; the layers run one after the other.  All arguments of
+ * all layers are validated before the first launch.
+ *
+ *   q, k_pools, v_pools, out   host arrays [num_layers] of device pointers, each
+ *                              as the argument of the same name above
+ *   num_layers                 >= 0; 0 is a no-op returning PKV_OK
+ * Everything else as for paged_decode_attn.
+ */
+int paged_decode_attn_layers(const void* const* q, const void* const* k_pools,
+                             const void* const* v_pools, const int32_t* block_tables,
+                             const int32_t* context_lens, float scale, void* const* out,
+                             int32_t num_layers, const pkv_attn_shape* shape, void* workspace,
+                             size_t workspace_bytes, void* stream);
+
+/*
  * staging[i] = pool[block_ids[i]] for i in [0, n_blocks): the send side of
  * evicting a preempted request's KV cache (paper Section II-B) or of shipping
  * a request's entire KV cache at the reasoning-to-answering transition

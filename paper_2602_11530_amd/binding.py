@@ -23,6 +23,7 @@ PKV_ERR_LAUNCH = -5
 
 EXPORTS = (
     "pkv_attn_partition_size", "pkv_attn_workspace_bytes", "paged_decode_attn",
+    "paged_decode_attn_layers",
     "kv_blocks_gather", "kv_blocks_scatter", "kv_append", "pkv_status_string",
     "pkv_last_launch_error", "pkv_version",
 )
@@ -78,6 +79,9 @@ def lib() -> ctypes.CDLL:
         L.paged_decode_attn.argtypes = [vp, vp, vp, i32p, i32p, ctypes.c_float, vp, shp, vp,
                                         ctypes.c_size_t, vp]
         L.paged_decode_attn.restype = ctypes.c_int
+        L.paged_decode_attn_layers.argtypes = [vp, vp, vp, i32p, i32p, ctypes.c_float, vp,
+                                               ctypes.c_int32, shp, vp, ctypes.c_size_t, vp]
+        L.paged_decode_attn_layers.restype = ctypes.c_int
         L.kv_blocks_gather.argtypes = [vp, i32p, vp, i64, i64, i64, vp]
         L.kv_blocks_gather.restype = ctypes.c_int
         L.kv_blocks_scatter.argtypes = [vp, vp, i32p, i64, i64, i64, vp]
@@ -140,6 +144,27 @@ def paged_decode_attn(q, k_pool, v_pool, block_tables, context_lens, scale, out,
                                    _ptr(context_lens), ctypes.c_float(scale), _ptr(out),
                                    ctypes.byref(shape), _ptr(workspace), ws_bytes,
                                    _stream(stream)))
+
+
+def pointer_array(tensors):
+    """Host array of the tensors' device pointers, as the multi-layer call takes it.
+    Build it once per model: the pools do not move between decode steps."""
+    return (ctypes.c_void_p * len(tensors))(*[int(t.data_ptr()) for t in tensors])
+
+
+def paged_decode_attn_layers(q, k_pools, v_pools, block_tables, context_lens, scale, out,
+                             shape: AttnShape, workspace=None, stream=None) -> None:
+    """All layers' attention of one decode step in one call.  ``q``, ``k_pools``,
+    ``v_pools`` and ``out`` are equally long lists of tensors or ``pointer_array``s."""
+    arrs = [a if isinstance(a, ctypes.Array) else pointer_array(a) for a in (q, k_pools, v_pools, out)]
+    n = len(arrs[0])
+    if any(len(a) != n for a in arrs):
+        raise ValueError("q, k_pools, v_pools and out must list the same number of layers")
+    ws_bytes = 0 if workspace is None else workspace.numel() * workspace.element_size()
+    _check(lib().paged_decode_attn_layers(arrs[0], arrs[1], arrs[2], _ptr(block_tables),
+                                          _ptr(context_lens), ctypes.c_float(scale), arrs[3], n,
+                                          ctypes.byref(shape), _ptr(workspace), ws_bytes,
+                                          _stream(stream)))
 
 
 def kv_blocks_gather(pool, block_ids, staging, n_blocks: int, block_bytes: int,

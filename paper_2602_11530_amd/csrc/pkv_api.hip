@@ -111,50 +111,97 @@ int pkv_attn_workspace_bytes(const pkv_attn_shape* shape, size_t* out_bytes) {
   return PKV_OK;
 }
 
-int paged_decode_attn(const void* q, const void* k_pool, const void* v_pool,
-                      const int32_t* block_tables, const int32_t* context_lens, float scale,
-                      void* out, const pkv_attn_shape* shape, void* workspace,
-                      size_t workspace_bytes_given, void* stream) {
+// Validation shared by the single-layer and the multi-layer call; fills the
+// launch descriptor except for the per-layer pointers.
+static int prepare_attn(const int32_t* block_tables, const int32_t* context_lens, float scale,
+                        const pkv_attn_shape* shape, void* workspace, size_t workspace_bytes_given,
+                        pkv::AttnLaunch* a, bool* empty) {
   Geometry g;
   const int rc = check_shape(shape, &g);
   if (rc != PKV_OK) return rc;
-  if (shape->num_seqs == 0) return PKV_OK;
-  if (!q || !k_pool || !v_pool || !block_tables || !context_lens || !out) return PKV_ERR_NULL;
-  if (misaligned16(q) || misaligned16(k_pool) || misaligned16(v_pool) || misaligned16(out) ||
-      (reinterpret_cast<uintptr_t>(block_tables) & 3u) || (reinterpret_cast<uintptr_t>(context_lens) & 3u))
+  *empty = shape->num_seqs == 0;
+  if (*empty) return PKV_OK;
+  if (!block_tables || !context_lens) return PKV_ERR_NULL;
+  if ((reinterpret_cast<uintptr_t>(block_tables) & 3u) || (reinterpret_cast<uintptr_t>(context_lens) & 3u))
     return PKV_ERR_ALIGN;
   const size_t need = workspace_bytes(shape, g);
   if (need) {
     if (!workspace || workspace_bytes_given < need) return PKV_ERR_WORKSPACE;
     if (misaligned16(workspace)) return PKV_ERR_ALIGN;
   }
+  a->block_tables = block_tables;
+  a->context_lens = context_lens;
+  a->S = shape->num_seqs;
+  a->Hq = shape->num_q_heads;
+  a->Hkv = shape->num_kv_heads;
+  a->G = g.G;
+  a->MAXB = shape->max_blocks_per_seq;
+  a->P = g.P;
+  a->max_ctx = g.max_ctx;
+  a->NB = (int)shape->num_pool_blocks;
+  a->scale_log2e = scale * 1.4426950408889634f;
+  const WorkspaceLayout lay = workspace_layout(shape, g);
+  char* ws = static_cast<char*>(workspace);
+  a->ws_rec = reinterpret_cast<float*>(ws);
+  a->ws_cum = reinterpret_cast<int32_t*>(ws + lay.rec_bytes);
+  return PKV_OK;
+}
 
-  pkv::AttnLaunch a;
+static int check_layer_pointers(const void* q, const void* k_pool, const void* v_pool, const void* out) {
+  if (!q || !k_pool || !v_pool || !out) return PKV_ERR_NULL;
+  if (misaligned16(q) || misaligned16(k_pool) || misaligned16(v_pool) || misaligned16(out))
+    return PKV_ERR_ALIGN;
+  return PKV_OK;
+}
+
+static int launch_layer(pkv::AttnLaunch& a, const void* q, const void* k_pool, const void* v_pool,
+                        void* out, hipStream_t st) {
   a.q = static_cast<const uint16_t*>(q);
   a.k_pool = static_cast<const uint16_t*>(k_pool);
   a.v_pool = static_cast<const uint16_t*>(v_pool);
-  a.block_tables = block_tables;
-  a.context_lens = context_lens;
   a.out = static_cast<uint16_t*>(out);
-  a.S = shape->num_seqs;
-  a.Hq = shape->num_q_heads;
-  a.Hkv = shape->num_kv_heads;
-  a.G = g.G;
-  a.MAXB = shape->max_blocks_per_seq;
-  a.P = g.P;
-  a.max_ctx = g.max_ctx;
-  a.NB = (int)shape->num_pool_blocks;
-  a.scale_log2e = scale * 1.4426950408889634f;
-  const WorkspaceLayout lay = workspace_layout(shape, g);
-  char* ws = static_cast<char*>(workspace);
-  a.ws_rec = reinterpret_cast<float*>(ws);
-  a.ws_cum = reinterpret_cast<int32_t*>(ws + lay.rec_bytes);
-
-  hipStream_t st = static_cast<hipStream_t>(stream);
   hipError_t e = pkv::launch_attn_stream(a, st);
   if (e != hipSuccess) return launch_status(e);
   e = pkv::launch_attn_reduce(a, st);
   if (e != hipSuccess) return launch_status(e);
+  return PKV_OK;
+}
+
+int paged_decode_attn(const void* q, const void* k_pool, const void* v_pool,
+                      const int32_t* block_tables, const int32_t* context_lens, float scale,
+                      void* out, const pkv_attn_shape* shape, void* workspace,
+                      size_t workspace_bytes_given, void* stream) {
+  pkv::AttnLaunch a;
+  bool empty = false;
+  int rc = prepare_attn(block_tables, context_lens, scale, shape, workspace, workspace_bytes_given,
+                        &a, &empty);
+  if (rc != PKV_OK || empty) return rc;
+  rc = check_layer_pointers(q, k_pool, v_pool, out);
+  if (rc != PKV_OK) return rc;
+  return launch_layer(a, q, k_pool, v_pool, out, static_cast<hipStream_t>(stream));
+}
+
+int paged_decode_attn_layers(const void* const* q, const void* const* k_pools,
+                             const void* const* v_pools, const int32_t* block_tables,
+                             const int32_t* context_lens, float scale, void* const* out,
+                             int32_t num_layers, const pkv_attn_shape* shape, void* workspace,
+                             size_t workspace_bytes_given, void* stream) {
+  if (num_layers < 0) return PKV_ERR_SHAPE;
+  pkv::AttnLaunch a;
+  bool empty = false;
+  int rc = prepare_attn(block_tables, context_lens, scale, shape, workspace, workspace_bytes_given,
+                        &a, &empty);
+  if (rc != PKV_OK || empty || num_layers == 0) return rc;
+  if (!q || !k_pools || !v_pools || !out) return PKV_ERR_NULL;
+  // every layer is checked before the first launch: an error enqueues nothing
+  for (int32_t l = 0; l < num_layers; ++l) {
+    rc = check_layer_pointers(q[l], k_pools[l], v_pools[l], out[l]);
+    if (rc != PKV_OK) return rc;
+  }
+  for (int32_t l = 0; l < num_layers; ++l) {
+    rc = launch_layer(a, q[l], k_pools[l], v_pools[l], out[l], static_cast<hipStream_t>(stream));
+    if (rc != PKV_OK) return rc;
+  }
   return PKV_OK;
 }
 

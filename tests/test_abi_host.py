@@ -121,3 +121,25 @@ def test_append_argument_errors_before_launch():
     assert call(16, 16, 16, 16, 16, 16, ctypes.byref(bad), None) == pkv.PKV_ERR_SHAPE
     sh0 = pkv.make_shape(0, 8, 2, 19, 128)
     assert call(None, None, None, None, None, None, ctypes.byref(sh0), None) == pkv.PKV_OK
+
+
+def test_layers_argument_errors_before_launch():
+    L = pkv.lib()
+    sh = pkv.make_shape(4, 8, 2, 19, 128, partition_size=16)
+    need = pkv.pkv_attn_workspace_bytes(sh)
+    arr = lambda *v: (ctypes.c_void_p * len(v))(*v)
+    good = arr(16, 32, 48)
+    call = lambda q, k, v, o, n, ws=16, nbytes=need, shape=sh, tables=16: L.paged_decode_attn_layers(
+        q, k, v, tables, 16, 1.0, o, n, ctypes.byref(shape), ws, nbytes, None)
+    assert call(good, good, good, good, -1) == pkv.PKV_ERR_SHAPE
+    assert call(None, None, None, None, 0) == pkv.PKV_OK
+    assert call(None, good, good, good, 3) == pkv.PKV_ERR_NULL
+    assert call(good, good, arr(16, None, 48), good, 3) == pkv.PKV_ERR_NULL
+    # a bad pointer in the last layer is found before anything is launched
+    assert call(good, good, good, arr(16, 32, 40), 3) == pkv.PKV_ERR_ALIGN
+    assert call(good, good, good, good, 3, nbytes=need - 1) == pkv.PKV_ERR_WORKSPACE
+    assert call(good, good, good, good, 3, tables=18) == pkv.PKV_ERR_ALIGN
+    bad = pkv.make_shape(4, 9, 2, 19, 128)
+    assert call(good, good, good, good, 3, shape=bad) == pkv.PKV_ERR_SHAPE
+    sh0 = pkv.make_shape(0, 8, 2, 19, 128)
+    assert call(None, None, None, None, 3, ws=None, nbytes=0, shape=sh0) == pkv.PKV_OK

@@ -89,20 +89,36 @@ def test_cfg4_full_depth_resident(device):
     ws = torch.empty(pkv.pkv_attn_workspace_bytes(shape), dtype=torch.uint8, device=device)
     outs = [torch.full(w.q_shape(), 0x7FC1, dtype=torch.int16, device=device) for _ in range(n_layers)]
 
-    def step():
+    ptrs = [pkv.pointer_array(x) for x in ([l[0] for l in layers], [l[1] for l in layers],
+                                           [l[2] for l in layers], outs)]
+
+    def step_single_calls():
         for (q, k, v), out in zip(layers, outs):
             pkv.paged_decode_attn(q, k, v, tables_d, lens_d, float(w.scale), out, shape, ws)
 
-    step()
-    torch.cuda.synchronize()
-    t0, t1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-    t0.record()
-    step()
-    t1.record()
-    torch.cuda.synchronize()
-    ms = t0.elapsed_time(t1)
+    def step_one_call():
+        pkv.paged_decode_attn_layers(ptrs[0], ptrs[1], ptrs[2], tables_d, lens_d, float(w.scale),
+                                     ptrs[3], shape, ws)
+
+    def timed(fn):
+        fn()
+        torch.cuda.synchronize()
+        t0, t1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        t0.record()
+        fn()
+        t1.record()
+        torch.cuda.synchronize()
+        return t0.elapsed_time(t1)
+
+    ms_single = timed(step_single_calls)
+    single = [o.clone() for o in outs]
+    for o in outs:
+        o.fill_(0x7FC1)
+    ms = timed(step_one_call)
+    assert all(torch.equal(a, b) for a, b in zip(outs, single)), "multi-layer call != single calls"
     gbps = w.attn_algorithmic_bytes() * n_layers / (ms * 1e-3) / 1e9
-    print(f"full-depth step: {ms:.2f} ms for {n_layers} layers, {gbps:.0f} GB/s algorithmic", flush=True)
+    print(f"full-depth step: {ms:.2f} ms for {n_layers} layers in one call ({gbps:.0f} GB/s algorithmic); "
+          f"{ms_single:.2f} ms as {n_layers} single calls", flush=True)
 
     rng = np.random.default_rng(w.seed + 99)
     full_layers = sorted(rng.choice(n_layers, size=min(2, n_layers), replace=False).tolist())
