@@ -32,6 +32,7 @@ extern "C" {
 #define PKV_ERR_ALIGN (-3)     /* a pointer or byte count is not 16-byte aligned      */
 #define PKV_ERR_WORKSPACE (-4) /* workspace missing or smaller than required          */
 #define PKV_ERR_LAUNCH (-5)    /* HIP refused the launch; see pkv_last_launch_error() */
+#define PKV_ERR_HOST (-6)      /* a host buffer of an offload/reload is not pinned memory */
 
 /* Sizes of one attention call.  The batch changes at every decode step
  * (continuous batching, paper Section II-B), so nothing here is fixed at
@@ -158,6 +159,36 @@ int kv_blocks_gather(const void* pool, const int32_t* block_ids, void* staging,
 int kv_blocks_scatter(const void* staging, void* pool, const int32_t* block_ids,
                       int64_t n_blocks, int64_t block_bytes, int64_t num_pool_blocks,
                       void* stream);
+
+/*
+ * Eviction of a preempted request to the backing store: the listed blocks are
+ * gathered into `staging` and that image is copied to page-locked host memory,
+ * both on `stream` (paper Section II-B: a preempted request's KV cache is
+ * offloaded to CPU memory, which serves only as backing storage, Section VII).
+ * After the stream reaches this point host_dst[i] is the byte image of
+ * pool[block_ids[i]] and the blocks may be handed to other requests.
+ *
+ *   pool, block_ids, staging, sizes   as for kv_blocks_gather (all device)
+ *   host_dst   host, pinned (hipHostMalloc or an equivalent allocator),
+ *              n_blocks * block_bytes bytes; PKV_ERR_HOST if it is anything else
+ * The device part runs at HBM speed; the host copy is bound by the PCIe link
+ * and is carried out by the copy engines, so decode attention on another stream
+ * keeps the compute units meanwhile.
+ */
+int kv_blocks_offload(const void* pool, const int32_t* block_ids, void* staging, void* host_dst,
+                      int64_t n_blocks, int64_t block_bytes, int64_t num_pool_blocks,
+                      void* stream);
+
+/*
+ * Resumption of a preempted request: the image saved by kv_blocks_offload is
+ * copied back into `staging` and scattered into freshly allocated blocks
+ * (Section II-B: the request resumes once memory is available, reloading its KV
+ * cache to the GPU).  Arguments as for kv_blocks_scatter plus the pinned host
+ * source; ids must be distinct.
+ */
+int kv_blocks_reload(const void* host_src, void* staging, void* pool, const int32_t* block_ids,
+                     int64_t n_blocks, int64_t block_bytes, int64_t num_pool_blocks,
+                     void* stream);
 
 /*
  * Writes the newly generated token's K and V rows into their slots: the step

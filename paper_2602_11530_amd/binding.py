@@ -20,11 +20,13 @@ PKV_ERR_SHAPE = -2
 PKV_ERR_ALIGN = -3
 PKV_ERR_WORKSPACE = -4
 PKV_ERR_LAUNCH = -5
+PKV_ERR_HOST = -6
 
 EXPORTS = (
     "pkv_attn_partition_size", "pkv_attn_workspace_bytes", "paged_decode_attn",
     "paged_decode_attn_layers",
-    "kv_blocks_gather", "kv_blocks_scatter", "kv_append", "pkv_status_string",
+    "kv_blocks_gather", "kv_blocks_scatter", "kv_blocks_offload", "kv_blocks_reload",
+    "kv_append", "pkv_status_string",
     "pkv_last_launch_error", "pkv_version",
 )
 
@@ -86,6 +88,10 @@ def lib() -> ctypes.CDLL:
         L.kv_blocks_gather.restype = ctypes.c_int
         L.kv_blocks_scatter.argtypes = [vp, vp, i32p, i64, i64, i64, vp]
         L.kv_blocks_scatter.restype = ctypes.c_int
+        L.kv_blocks_offload.argtypes = [vp, i32p, vp, vp, i64, i64, i64, vp]
+        L.kv_blocks_offload.restype = ctypes.c_int
+        L.kv_blocks_reload.argtypes = [vp, vp, vp, i32p, i64, i64, i64, vp]
+        L.kv_blocks_reload.restype = ctypes.c_int
         L.kv_append.argtypes = [vp, vp, vp, vp, i32p, i32p, shp, vp]
         L.kv_append.restype = ctypes.c_int
         _lib = L
@@ -177,6 +183,20 @@ def kv_blocks_scatter(staging, pool, block_ids, n_blocks: int, block_bytes: int,
                       num_pool_blocks: int, stream=None) -> None:
     _check(lib().kv_blocks_scatter(_ptr(staging), _ptr(pool), _ptr(block_ids), n_blocks,
                                    block_bytes, num_pool_blocks, _stream(stream)))
+
+
+def kv_blocks_offload(pool, block_ids, staging, host_dst, n_blocks: int, block_bytes: int,
+                      num_pool_blocks: int, stream=None) -> None:
+    """Gather the listed blocks and copy the image to the pinned host tensor ``host_dst``."""
+    _check(lib().kv_blocks_offload(_ptr(pool), _ptr(block_ids), _ptr(staging), _ptr(host_dst),
+                                   n_blocks, block_bytes, num_pool_blocks, _stream(stream)))
+
+
+def kv_blocks_reload(host_src, staging, pool, block_ids, n_blocks: int, block_bytes: int,
+                     num_pool_blocks: int, stream=None) -> None:
+    """Copy a saved image from the pinned host tensor and scatter it into the listed blocks."""
+    _check(lib().kv_blocks_reload(_ptr(host_src), _ptr(staging), _ptr(pool), _ptr(block_ids),
+                                  n_blocks, block_bytes, num_pool_blocks, _stream(stream)))
 
 
 def kv_append(k_new, v_new, k_pool, v_pool, block_tables, context_lens, shape: AttnShape,

@@ -90,6 +90,7 @@ const char* pkv_status_string(int status) {
     case PKV_ERR_ALIGN: return "a pointer or byte count is not 16-byte aligned";
     case PKV_ERR_WORKSPACE: return "workspace missing or too small";
     case PKV_ERR_LAUNCH: return "HIP refused the launch";
+    case PKV_ERR_HOST: return "the host buffer is not pinned host memory";
     default: return "unknown status";
   }
 }
@@ -224,16 +225,38 @@ int kv_append(const void* k_new, const void* v_new, void* k_pool, void* v_pool,
   return launch_status(e);
 }
 
-static int copy_call(const void* pool, const void* staging, const int32_t* block_ids,
-                     int64_t n_blocks, int64_t block_bytes, int64_t num_pool_blocks, bool gather,
-                     void* stream) {
+// Host-visible checks of a block copy; *empty is set when there is nothing to do.
+static int check_copy(const void* pool, const void* staging, const int32_t* block_ids,
+                      int64_t n_blocks, int64_t block_bytes, int64_t num_pool_blocks, bool* empty) {
+  *empty = false;
   if (n_blocks < 0 || block_bytes <= 0 || num_pool_blocks < 0) return PKV_ERR_SHAPE;
   if (block_bytes % 16 != 0) return PKV_ERR_ALIGN;
   if (n_blocks > INT32_MAX || block_bytes > ((int64_t)1 << 30)) return PKV_ERR_SHAPE;
-  if (n_blocks == 0) return PKV_OK;
+  *empty = n_blocks == 0;
+  if (*empty) return PKV_OK;
   if (!pool || !staging || !block_ids) return PKV_ERR_NULL;
   if (misaligned16(pool) || misaligned16(staging) || (reinterpret_cast<uintptr_t>(block_ids) & 3u))
     return PKV_ERR_ALIGN;
+  return PKV_OK;
+}
+
+// The far end of an offload or reload must be page-locked host memory: only
+// then is the copy asynchronous and done by the DMA engines at link speed.
+static int check_pinned(const void* host) {
+  hipPointerAttribute_t attr;
+  if (hipPointerGetAttributes(&attr, host) != hipSuccess) {
+    (void)hipGetLastError();   // an unknown pointer is reported as an error; clear it
+    return PKV_ERR_HOST;
+  }
+  return attr.type == hipMemoryTypeHost ? PKV_OK : PKV_ERR_HOST;
+}
+
+static int copy_call(const void* pool, const void* staging, const int32_t* block_ids,
+                     int64_t n_blocks, int64_t block_bytes, int64_t num_pool_blocks, bool gather,
+                     void* stream) {
+  bool empty = false;
+  const int rc = check_copy(pool, staging, block_ids, n_blocks, block_bytes, num_pool_blocks, &empty);
+  if (rc != PKV_OK || empty) return rc;
   hipStream_t st = static_cast<hipStream_t>(stream);
   const hipError_t e =
       gather ? pkv::launch_kv_block_copy(pool, const_cast<void*>(staging), block_ids, n_blocks,
@@ -251,6 +274,40 @@ int kv_blocks_gather(const void* pool, const int32_t* block_ids, void* staging, 
 int kv_blocks_scatter(const void* staging, void* pool, const int32_t* block_ids, int64_t n_blocks,
                       int64_t block_bytes, int64_t num_pool_blocks, void* stream) {
   return copy_call(pool, staging, block_ids, n_blocks, block_bytes, num_pool_blocks, false, stream);
+}
+
+int kv_blocks_offload(const void* pool, const int32_t* block_ids, void* staging, void* host_dst,
+                      int64_t n_blocks, int64_t block_bytes, int64_t num_pool_blocks, void* stream) {
+  bool empty = false;
+  int rc = check_copy(pool, staging, block_ids, n_blocks, block_bytes, num_pool_blocks, &empty);
+  if (rc != PKV_OK || empty) return rc;
+  if (!host_dst) return PKV_ERR_NULL;
+  rc = check_pinned(host_dst);
+  if (rc != PKV_OK) return rc;
+  hipStream_t st = static_cast<hipStream_t>(stream);
+  hipError_t e = pkv::launch_kv_block_copy(pool, staging, block_ids, n_blocks, block_bytes,
+                                           num_pool_blocks, true, st);
+  if (e != hipSuccess) return launch_status(e);
+  e = hipMemcpyAsync(host_dst, staging, (size_t)n_blocks * (size_t)block_bytes,
+                     hipMemcpyDeviceToHost, st);
+  return launch_status(e);
+}
+
+int kv_blocks_reload(const void* host_src, void* staging, void* pool, const int32_t* block_ids,
+                     int64_t n_blocks, int64_t block_bytes, int64_t num_pool_blocks, void* stream) {
+  bool empty = false;
+  int rc = check_copy(pool, staging, block_ids, n_blocks, block_bytes, num_pool_blocks, &empty);
+  if (rc != PKV_OK || empty) return rc;
+  if (!host_src) return PKV_ERR_NULL;
+  rc = check_pinned(host_src);
+  if (rc != PKV_OK) return rc;
+  hipStream_t st = static_cast<hipStream_t>(stream);
+  hipError_t e = hipMemcpyAsync(staging, host_src, (size_t)n_blocks * (size_t)block_bytes,
+                                hipMemcpyHostToDevice, st);
+  if (e != hipSuccess) return launch_status(e);
+  e = pkv::launch_kv_block_copy(staging, pool, block_ids, n_blocks, block_bytes, num_pool_blocks,
+                                false, st);
+  return launch_status(e);
 }
 
 }  // extern "C"

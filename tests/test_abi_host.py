@@ -32,8 +32,8 @@ def test_shape_struct_layout():
 
 def test_status_strings():
     L = pkv.lib()
-    seen = {L.pkv_status_string(c) for c in range(0, -6, -1)}
-    assert len(seen) == 6 and b"unknown status" not in seen
+    seen = {L.pkv_status_string(c) for c in range(0, -7, -1)}
+    assert len(seen) == 7 and b"unknown status" not in seen
     assert L.pkv_status_string(-99) == b"unknown status"
 
 
@@ -143,3 +143,22 @@ def test_layers_argument_errors_before_launch():
     assert call(good, good, good, good, 3, shape=bad) == pkv.PKV_ERR_SHAPE
     sh0 = pkv.make_shape(0, 8, 2, 19, 128)
     assert call(None, None, None, None, 3, ws=None, nbytes=0, shape=sh0) == pkv.PKV_OK
+
+
+def test_offload_reload_argument_errors_before_launch():
+    L = pkv.lib()
+    # offload(pool, ids, staging, host, ...), reload(host, staging, pool, ids, ...)
+    off = lambda pool, ids, stg, host, *a: L.kv_blocks_offload(pool, ids, stg, host, *a, None)
+    rel = lambda pool, ids, stg, host, *a: L.kv_blocks_reload(host, stg, pool, ids, *a, None)
+    for fn in (off, rel):
+        assert fn(None, None, None, None, 0, 32768, 64) == pkv.PKV_OK
+        assert fn(16, 16, 16, 16, -1, 32768, 64) == pkv.PKV_ERR_SHAPE
+        assert fn(16, 16, 16, 16, 4, 40, 64) == pkv.PKV_ERR_ALIGN
+        assert fn(None, 16, 16, 16, 4, 32768, 64) == pkv.PKV_ERR_NULL
+        assert fn(16, 16, None, 16, 4, 32768, 64) == pkv.PKV_ERR_NULL
+        assert fn(16, 16, 16, None, 4, 32768, 64) == pkv.PKV_ERR_NULL
+        assert fn(16, 18, 16, 16, 4, 32768, 64) == pkv.PKV_ERR_ALIGN
+        # an address that is not page-locked host memory is refused, nothing is enqueued
+        assert fn(16, 16, 16, 4096, 4, 32768, 64) == pkv.PKV_ERR_HOST
+        buf = ctypes.create_string_buffer(4 * 32768)
+        assert fn(16, 16, 16, ctypes.addressof(buf), 4, 32768, 64) == pkv.PKV_ERR_HOST
