@@ -26,8 +26,8 @@ HBM_PEAK_GBPS = 8000.0   # MI355X published HBM3E bandwidth
 # HBM bytes per launch of the stream kernel from rocprofv3 FETCH_SIZE + WRITE_SIZE, each scaled by
 # what the same counter reads for the copy kernel of known size (profiles/attn_stream_cfg2.md,
 # profiles/attn_stream_cfg3.md); quoted only for the partitioning those profiles were taken with.
-MEASURED_TRAFFIC_BYTES = {"cfg2_qwen32b_b64_u1024_8192": 1219940000,
-                          "cfg3_longcot_b128_lognormal": 4114370000}
+MEASURED_TRAFFIC_BYTES = {"cfg2_qwen32b_b64_u1024_8192": 1219560000,
+                          "cfg3_longcot_b128_lognormal": 4110160000}
 
 
 def parse():
