@@ -288,3 +288,31 @@ def make_host_tensors(w: Workload, layer: int = 0, poison_unused: bool = False):
         k[mask[:, None, :, None].repeat(w.num_kv_heads, 1).repeat(w.head_dim, 3)] = BF16_NAN
         v[mask[:, None, :, None].repeat(w.num_kv_heads, 1).repeat(w.head_dim, 3)] = BF16_INF
     return q, k, v
+
+
+@dataclass
+class ServingTrace:
+    """Synthetic request trace for the scheduler: arrival times (seconds,
+    ascending) and, per request, the prompt length and the number of reasoning
+    and answering tokens the model will emit (the last reasoning token is the
+    end-of-reasoning marker, the last answering token ends the sequence)."""
+    arrival: np.ndarray
+    prompt: np.ndarray
+    reasoning: np.ndarray
+    answering: np.ndarray
+    seed: int
+
+    def __len__(self) -> int:
+        return len(self.arrival)
+
+
+def serving_trace(n_requests: int = 300, rate_per_s: float = 4.0, prompt: int = 128,
+                  lo: int = 128, hi: int = 2048, seed: int = BASE_SEED + 6) -> ServingTrace:
+    """Poisson arrivals; fixed prompt length; reasoning and answering lengths
+    uniform in [lo, hi] — the shape of the paper's synthetic characterization
+    workload (Section III-A: 300 requests, prompt 128, 128..2048 tokens per phase)."""
+    rng = np.random.default_rng(seed)
+    arrival = np.cumsum(rng.exponential(1.0 / rate_per_s, size=n_requests))
+    return ServingTrace(arrival, np.full(n_requests, prompt, np.int32),
+                        rng.integers(lo, hi + 1, size=n_requests).astype(np.int32),
+                        rng.integers(lo, hi + 1, size=n_requests).astype(np.int32), seed)

@@ -1,0 +1,244 @@
+"""Pins of the scheduler oracle (CPU only): the two instance-selection algorithms on
+worked tables, the adaptive-migration example, closed forms for the QoE measure, and
+invariants of the queue dynamics on seeded traces."""
+import itertools
+
+import numpy as np
+import pytest
+
+from oracle import pascal_oracle as po
+from paper_2602_11530_amd import workloads as wl
+
+from serving_driver import replay
+
+
+# ---- Algorithm 1 (instance selection for reasoning requests) ---------------------
+
+def test_alg1_worked_tables():
+    f = po.select_reasoning_instance
+    # smallest KV footprint among the instances that meet their answering SLO
+    assert f([True, True, True], [7, 3, 5]) == 1
+    assert f([True, False, True], [7, 3, 5]) == 2      # instance 1 is excluded although it is the emptiest
+    assert f([False, False, True], [1, 2, 900]) == 2   # a single candidate wins whatever its footprint
+    # nobody meets the SLO: fall back to all instances
+    assert f([False, False, False], [7, 3, 5]) == 1
+    assert f([True] * 4, [4, 2, 2, 9]) == 1            # tie: lowest index
+
+
+def test_alg1_against_exhaustive_definition():
+    rng = np.random.default_rng(1)
+    for _ in range(300):
+        n = int(rng.integers(1, 9))
+        t = rng.random(n) < 0.6
+        m = rng.integers(0, 6, size=n)
+        cand = [i for i in range(n) if t[i]] or list(range(n))
+        got = po.select_reasoning_instance(list(t), list(m))
+        assert got in cand and all(m[got] <= m[i] for i in cand)
+        assert all(m[i] > m[got] for i in cand if i < got)
+
+
+# ---- Algorithm 2 (instance selection for answering requests) --------------------
+
+def test_alg2_worked_tables():
+    f = po.select_answering_instance
+    # fewest reasoning requests among SLO-compliant instances; a_i plays no part there
+    assert f([True, True, True], [4, 1, 2], [0, 50, 0]) == 1
+    assert f([True, False, True], [4, 1, 2], [0, 0, 0]) == 2
+    # nobody compliant: r_i + a_i decides
+    assert f([False] * 3, [4, 1, 2], [0, 5, 1]) == 2    # 4, 6, 3
+    assert f([False] * 3, [4, 1, 2], [0, 0, 9]) == 1    # 4, 1, 11
+    # r alone would pick 1, r + a picks 0
+    assert f([False] * 2, [3, 2], [0, 2]) == 0
+    # ties: stay where you are, else lowest index
+    assert f([True] * 3, [2, 2, 2], [0, 0, 0], current=2) == 2
+    assert f([True] * 3, [2, 2, 2], [0, 0, 0], current=None) == 0
+    assert f([True, True, False], [2, 2, 0], [0, 0, 0], current=2) == 0   # current is not a candidate
+
+
+def test_alg2_against_exhaustive_definition():
+    rng = np.random.default_rng(2)
+    for _ in range(300):
+        n = int(rng.integers(1, 9))
+        t = rng.random(n) < 0.5
+        r, a = rng.integers(0, 5, size=n), rng.integers(0, 5, size=n)
+        cur = int(rng.integers(0, n))
+        if t.any():
+            cand, key = [i for i in range(n) if t[i]], r
+        else:
+            cand, key = list(range(n)), r + a
+        got = po.select_answering_instance(list(t), list(r), list(a), current=cur)
+        assert got in cand and all(key[got] <= key[i] for i in cand)
+        if cur in cand and key[cur] == key[got]:
+            assert got == cur
+
+
+# ---- adaptive migration (Section IV-B, the example of its figure) -------------------
+
+def test_adaptive_migration_example():
+    """Instance 2 holds the answering requests and its memory is full; instance 0, where
+    the request finished reasoning, still has two free slots: Algorithm 2 says 2, the
+    override keeps the request on 0."""
+    t, r, a = [True] * 3, [2, 1, 0], [0, 0, 3]
+    sel = po.select_answering_instance(t, r, a, current=0)
+    assert sel == 2
+    assert po.adaptive_migration(0, sel, free_current=2, free_selected=0, request_blocks=1, headroom=1) == 0
+    # with room at the destination the migration goes ahead
+    assert po.adaptive_migration(0, sel, free_current=2, free_selected=4, request_blocks=1, headroom=1) == 2
+    # neither has room: Algorithm 2's choice stands
+    assert po.adaptive_migration(0, sel, free_current=0, free_selected=0, request_blocks=1, headroom=1) == 2
+    assert po.adaptive_migration(1, 1, 0, 0, 5, 1) == 1
+
+
+# ---- QoE and the pacer -----------------------------------------------------------------
+
+def test_qoe_closed_forms():
+    tp = 0.1
+    on_pace = [2.0 + k * tp for k in range(50)]
+    assert po.qoe(on_pace, tp) == pytest.approx(1.0, abs=1e-12)
+    # faster than the reader: the pacer buffers, the reader is never starved
+    burst = [2.0 + k * 0.01 for k in range(50)]
+    assert po.qoe(burst, tp) == pytest.approx(1.0, abs=1e-12)
+    assert po.digest_times(burst, tp) == pytest.approx(on_pace)
+    # two tokens, the second three periods late: digested area 3, expected area 3 + 2
+    assert po.qoe([0.0, 3.0], 1.0) == pytest.approx(0.6)
+    # a pause of `gap` after token j delays every later token by gap - (buffer drained)
+    N, j, gap = 20, 7, 2.5
+    g = [k * 1.0 for k in range(j + 1)] + [j + gap + (k - j - 1) * 1.0 for k in range(j + 1, N)]
+    d = po.digest_times(g, 1.0)
+    late = gap - 1.0
+    assert d[: j + 1] == pytest.approx(list(range(j + 1)))
+    assert d[j + 1:] == pytest.approx([k + late for k in range(j + 1, N)])
+    T = N - 1 + late
+    want = sum(T - x for x in d) / sum(T - k for k in range(N))
+    assert po.qoe(g, 1.0) == pytest.approx(want) and want < 1
+    # bounds and monotonicity: more delay never raises the score
+    rng = np.random.default_rng(3)
+    for _ in range(100):
+        gaps = rng.exponential(0.1, size=30)
+        g = list(np.cumsum(gaps))
+        s = po.qoe(g, tp)
+        assert 0 < s <= 1 + 1e-12
+        g2 = g[:10] + [x + 0.7 for x in g[10:]]
+        assert po.qoe(g2, tp) <= s + 1e-12
+    assert po.qoe([], tp) == 1.0 and po.qoe([5.0], tp) == 1.0
+
+
+def test_pacer_lagging():
+    # first token at 10.0, pace 0.1: by 10.35 the reader expects tokens 0..3
+    assert not po.pacer_lagging(4, 10.0, 10.35, 0.1)
+    assert po.pacer_lagging(3, 10.0, 10.35, 0.1)
+    assert not po.pacer_lagging(0, 0.0, 99.0, 0.1)     # no answering token yet: no pace to hold
+    assert not po.pacer_lagging(1, 10.0, 10.0, 0.1)
+
+
+# ---- queue dynamics: invariants on seeded traces ----------------------------------------
+
+class Checked(po.Cluster):
+    """The oracle with every invariant asserted after each call."""
+
+    def check(self, i):
+        cfg, ins = self.cfg, self.inst[i]
+        held = [b for rid in list(ins.high) + list(ins.low) for b in self.req[rid].blocks]
+        assert len(held) == len(set(held)), "a block belongs to two requests"
+        assert sorted(held + ins.free) == list(range(cfg.gpu_blocks)), "blocks leaked or invented"
+        for rid in ins.high:
+            q = self.req[rid]
+            assert q.level == po.HIGH and q.phase == po.REASONING and q.instance == i
+        for rid in ins.low:
+            q = self.req[rid]
+            assert q.level == po.LOW and q.instance == i
+            assert q.phase == po.ANSWERING or q.kv_tokens > cfg.demote_tokens
+        for rid in list(ins.high) + list(ins.low):
+            q = self.req[rid]
+            if q.state == po.RESIDENT:
+                assert len(q.blocks) >= self.blocks_for(q.kv_tokens) and q.offloaded_blocks == 0
+            elif q.state == po.OFFLOADED:
+                assert not q.blocks and q.offloaded_blocks == self.blocks_for(q.kv_tokens)
+            else:
+                assert q.state == po.QUEUED and (not q.blocks or rid in ins.selected)
+
+    def plan(self, i):
+        before = {rid: self.req[rid].state for rid in list(self.inst[i].high) + list(self.inst[i].low)}
+        order = list(self.inst[i].high) + list(self.inst[i].low)
+        rids, lens, ops = super().plan(i)
+        self.check(i)
+        # priority: nobody is evicted in favour of a request behind it in the order
+        first_evicted = min((order.index(op[2]) for op in ops if op[0] == po.OP_OFFLOAD), default=None)
+        if first_evicted is not None:
+            gained = [order.index(op[2]) for op in ops
+                      if op[0] in (po.OP_PREFILL, po.OP_RELOAD, po.OP_GROW)]
+            assert gained and min(gained) < first_evicted
+            # and everything ahead of the first victim that was resident stayed resident
+            for rid in order[:first_evicted]:
+                if before[rid] == po.RESIDENT:
+                    assert self.req[rid].state == po.RESIDENT
+        # each run of evictions serves the request whose op follows it: never one of lower priority
+        victims = []
+        for op in ops:
+            if op[0] == po.OP_OFFLOAD:
+                victims.append(op[2])
+            elif victims:
+                for v in victims:
+                    assert self.req[op[2]].level <= self.req[v].level, "evicted for a lower-priority request"
+                    assert order.index(op[2]) < order.index(v)
+                victims = []
+        assert not victims, "an eviction served nobody"
+        assert len(set(rids)) == len(rids)
+        for rid, L in zip(rids, lens):
+            q = self.req[rid]
+            assert len(q.blocks) == self.blocks_for(L)
+        return rids, lens, ops
+
+    def commit(self, i, now, kinds):
+        ops = super().commit(i, now, kinds)
+        for j in range(self.cfg.num_instances):
+            self.check(j)
+        return ops
+
+
+@pytest.mark.parametrize("gpu_blocks,rate", [(4000, 4.0), (700, 6.0), (300, 3.0)])
+def test_queue_dynamics_invariants(gpu_blocks, rate):
+    """Ample memory, pressure, and severe pressure (one long request nearly fills an instance)."""
+    trace = wl.serving_trace(n_requests=40, rate_per_s=rate, seed=wl.BASE_SEED + 60)
+    cfg = po.Config(num_instances=3, gpu_blocks=gpu_blocks, quantum=500, demote_tokens=3000)
+    c = Checked(cfg)
+    log = replay(c, trace, cfg.num_instances)
+    n_off = sum(1 for e in log if e[0] == "plan" for op in e[4] if op[0] == po.OP_OFFLOAD)
+    n_rel = sum(1 for e in log if e[0] == "plan" for op in e[4] if op[0] == po.OP_RELOAD)
+    n_mig = sum(1 for e in log if e[0] == "commit" for op in e[4] if op[0] in (po.OP_MIGRATE, po.OP_MIGRATE_HOST))
+    print(f"blocks={gpu_blocks}: offloads {n_off}, reloads {n_rel}, migrations {n_mig}")
+    if gpu_blocks == 4000:
+        assert n_off == 0
+    else:
+        assert n_off > 0 and n_rel > 0
+    for rid, q in enumerate(c.req):
+        assert q.state == po.FINISHED and not q.blocks
+        assert q.reasoning_tokens == trace.reasoning[rid]
+        assert len(q.answer_times) == trace.answering[rid]
+        assert q.kv_tokens == trace.prompt[rid] + trace.reasoning[rid] + trace.answering[rid] - 1
+        assert c.ttft(rid) > 0 and 0 < c.qoe(rid) <= 1 + 1e-12
+    for ins in c.inst:
+        assert not ins.high and not ins.low and len(ins.free) == gpu_blocks
+    # every offload is answered by exactly one reload or host-side hand-over of the same request
+    assert n_off == n_rel - sum(1 for e in log if e[0] == "commit" for op in e[4] if op[0] == po.OP_MIGRATE_HOST)
+
+
+def test_reasoning_is_never_evicted_for_answering():
+    """One instance under pressure: reasoning requests take turns among themselves, an
+    answering request is pushed out when they need its memory, never the reverse."""
+    cfg = po.Config(num_instances=1, gpu_blocks=48, quantum=50, demote_tokens=10**9)
+    c = Checked(cfg)
+    a, _ = c.submit(160, 0.0)     # 10 blocks each, growing
+    b, _ = c.submit(160, 0.0)
+    now, evicted_levels = 0.0, []
+    for step in range(260):
+        rids, lens, ops = c.plan(0)
+        evicted_levels += [(c.req[op[2]].level, c.req[op[2]].phase) for op in ops if op[0] == po.OP_OFFLOAD]
+        now += 0.03
+        kinds = [po.END_OF_REASONING if (r == a and step == 20) else po.TOKEN for r in rids]
+        c.commit(0, now, kinds)
+        if step == 25:
+            c.submit(200, now)    # a newcomer: high priority, may push the answering request out
+    assert c.req[a].phase == po.ANSWERING and c.req[b].phase == po.REASONING
+    assert c.req[a].preemptions > 0, "the scenario should put the answering request under pressure"
+    assert (po.LOW, po.ANSWERING) in evicted_levels
