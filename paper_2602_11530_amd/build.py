@@ -1,4 +1,5 @@
-"""Builds libpkv.so (gfx950) in-tree with hipcc.  ``python -m paper_2602_11530_amd.build``."""
+"""Builds libpkv.so (gfx950, hipcc) and libpascal_sched.so (host only, g++) in-tree.
+``python -m paper_2602_11530_amd.build``."""
 from __future__ import annotations
 
 import os
@@ -23,15 +24,34 @@ FLAGS = [
 ]
 
 
-def build(verbose: bool = True, extra_flags=()) -> str:
-    """Compile every HIP source; always recompiles (seconds)."""
-    tmp = LIB + f".tmp{os.getpid()}"
-    cmd = [HIPCC, *FLAGS, *extra_flags, "-o", tmp] + [os.path.join(CSRC, s) for s in SOURCES]
+SCHED_LIB = os.path.join(PKG, "libpascal_sched.so")
+SCHED_SOURCES = ["pascal_sched.cpp"]
+CXX = os.environ.get("CXX", "g++")
+# no fused multiply-add contraction: the QoE measure is compared bit for bit with the checker's
+SCHED_FLAGS = ["-O2", "-std=c++17", "-fPIC", "-shared", "-ffp-contract=off", "-Wall", "-Wextra"]
+
+
+def _compile(cmd, out, verbose):
+    tmp = out + f".tmp{os.getpid()}"
+    cmd = cmd + ["-o", tmp]
     if verbose:
         print(" ".join(cmd), flush=True)
     subprocess.check_call(cmd)
-    os.replace(tmp, LIB)
-    return LIB
+    os.replace(tmp, out)
+    return out
+
+
+def build_sched(verbose: bool = True) -> str:
+    """The host-side scheduler library: plain C++, no GPU code."""
+    return _compile([CXX, *SCHED_FLAGS] + [os.path.join(CSRC, s) for s in SCHED_SOURCES],
+                    SCHED_LIB, verbose)
+
+
+def build(verbose: bool = True, extra_flags=()) -> str:
+    """Compile every source of both libraries; always recompiles (seconds)."""
+    build_sched(verbose)
+    return _compile([HIPCC, *FLAGS, *extra_flags] + [os.path.join(CSRC, s) for s in SOURCES],
+                    LIB, verbose)
 
 
 if __name__ == "__main__":
