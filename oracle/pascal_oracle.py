@@ -16,7 +16,7 @@ What follows the paper directly (Section IV), in its notation:
   requests in the low-priority one, round-robin inside each with a token
   quantum (500 in Section V-A); a reasoning request whose KV cache exceeds a
   threshold (5000 tokens) is demoted to the low-priority queue (Section IV-C).
-* ``qoe`` — Section II-C, Fig. 4: area under the user-digested token curve over
+* ``qoe`` — Section II-C (its QoE figure): area under the user-digested token curve over
   the area under the user-expected curve, computed from TPOT only and starting
   at the first answering token (Section V-A, "Metric").
 * t_i — Section IV-B: an instance violates its answering SLO when its token
@@ -24,7 +24,7 @@ What follows the paper directly (Section IV), in its notation:
 
 Where the paper is silent this file takes the readings listed in the design
 notes; each is marked "reading" below.  Pins (tests/test_pascal_oracle.py):
-worked tables for both algorithms, the adaptive-migration example of Fig. 6,
+worked tables for both algorithms, the adaptive-migration example of the figure in Section IV-B,
 closed forms for QoE, and invariants of the queue dynamics on seeded traces
 (capacity never exceeded, block ids unique, priority respected, every token
 accounted for).  The queue dynamics beyond those invariants follow readings,
@@ -90,7 +90,7 @@ def adaptive_migration(current: int, selected: int, free_current: int, free_sele
 
 def digest_times(g: Sequence[float], tpot: float) -> List[float]:
     """When the user reads each answering token: no faster than one per `tpot`
-    and never before it exists (the pacer buffers early tokens, Fig. 4)."""
+    and never before it exists (the pacer buffers early tokens, Section II-C)."""
     d: List[float] = []
     for k, gk in enumerate(g):
         d.append(gk if k == 0 else max(gk, d[-1] + tpot))
