@@ -162,3 +162,36 @@ def test_offload_reload_argument_errors_before_launch():
         assert fn(16, 16, 16, 4096, 4, 32768, 64) == pkv.PKV_ERR_HOST
         buf = ctypes.create_string_buffer(4 * 32768)
         assert fn(16, 16, 16, ctypes.addressof(buf), 4, 32768, 64) == pkv.PKV_ERR_HOST
+
+
+def test_headers_are_plain_c(tmp_path):
+    """Both public headers compile as strict C99 and a C program links against the libraries."""
+    import subprocess
+    src = tmp_path / "use_abi.c"
+    src.write_text(r'''
+#include <stdio.h>
+#include "pkv.h"
+#include "pascal_sched.h"
+int main(void) {
+  pkv_attn_shape sh = {4, 8, 2, 128, 16, 19, 0, 0, 128};
+  size_t bytes = 0;
+  pascal_config cfg = {2, 64, 16, 500, 5000, 1, 0, 0, 0.1};
+  pascal_sched* s = 0;
+  int32_t rid = -1, inst = -1;
+  if (pkv_attn_workspace_bytes(&sh, &bytes) != PKV_OK || bytes == 0) return 1;
+  if (kv_blocks_gather(0, 0, 0, 0, 32768, 4, 0) != PKV_OK) return 2;
+  if (pascal_create(&cfg, &s) != PASCAL_OK) return 3;
+  if (pascal_submit(s, 40, 0.0, &rid, &inst) != PASCAL_OK || rid != 0) return 4;
+  pascal_destroy(s);
+  printf("%d %s\n", pkv_version(), pascal_status_string(0));
+  return 0;
+}
+''')
+    exe = tmp_path / "use_abi"
+    pkg = os.path.join(ROOT, "paper_2602_11530_amd")
+    subprocess.check_call(["gcc", "-std=c99", "-pedantic", "-Wall", "-Wextra", "-Werror",
+                           "-I", os.path.join(ROOT, "include"), str(src), "-o", str(exe),
+                           "-L", pkg, "-lpkv", "-lpascal_sched", f"-Wl,-rpath,{pkg}",
+                           "-Wl,-rpath,/opt/rocm/lib", "-L/opt/rocm/lib"])
+    out = subprocess.check_output([str(exe)]).decode().split()
+    assert int(out[0]) >= 1000 and out[1] == "ok"
