@@ -13,6 +13,7 @@
  *     bf16 [num_pool_blocks][num_kv_heads][block_size][head_dim], row-major,
  * so one physical block is one contiguous image of
  *     num_kv_heads * block_size * head_dim * 2 bytes  (32 KiB at 8 x 16 x 128).
+ * block_size is 16, 32 or 64 tokens; head_dim is 128.
  *
  * Status codes: 0 = PKV_OK; negative = error, nothing was enqueued.
  */
@@ -43,7 +44,7 @@ typedef struct {
   int32_t num_kv_heads;       /* Hkv; Hq % Hkv == 0; query heads h*G..h*G+G-1 share
                                  KV head h (G = Hq/Hkv, 1 <= G <= 16)                    */
   int32_t head_dim;           /* D: 128                                                  */
-  int32_t block_size;         /* B: 16 tokens per physical block                         */
+  int32_t block_size;         /* B: tokens per physical block: 16, 32 or 64              */
   int32_t max_blocks_per_seq; /* MAXB: row stride of block_tables, >= ceil(L_s/B)        */
   int32_t partition_size;     /* P: most tokens of a request that one partial result may
                                  cover before the split-K merge: a multiple of B in
@@ -52,7 +53,7 @@ typedef struct {
                                  MAXB*B.  A smaller bound only shrinks the launch;
                                  a request longer than the bound is attended up to it.   */
   int64_t num_pool_blocks;    /* NB: physical blocks in k_pool and in v_pool;
-                                 1 <= NB and NB * Hkv < 2^31                             */
+                                 1 <= NB and NB * Hkv * B/16 < 2^31                      */
 } pkv_attn_shape;
 
 /* The split-K partition size (tokens) a call with this shape will use:

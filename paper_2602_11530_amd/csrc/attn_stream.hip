@@ -90,7 +90,7 @@ __device__ __forceinline__ void store_record16(float* p, f32x4 v) {
 
 // One window of block descriptors: lane i describes stream index jbase + i.
 struct Window {
-  int slab;   // phys * Hkv + kvh: which 4 KiB (block, KV head) slab; 0 when the block is not read
+  int slab;   // which 4 KiB slab (16 tokens of one KV head), in slabs from the pool's start; 0 when not read
   int meta;   // bits 0-7 valid tokens (0..16), bit 8 closes a run, bit 9 first block of a segment here
   int qrow;   // s * Hq + kvh * G: first query/output row of the segment
   int slot;   // partial-record slot of the run this block belongs to
@@ -167,11 +167,13 @@ __global__ __launch_bounds__(kStreamWavesPerGroup * 64) void attn_stream_kernel(
     const int b = o - kvh * nb;
     const int nps = cumNP[s + 1] - cumNP[s];
     int ntok = min(kBlockTokens, lens[s] - kBlockTokens * b);
-    const int id = live ? a.block_tables[(int64_t)s * a.MAXB + b] : -1;
+    // unit b of the request lies in physical block b / upb, at unit b % upb of the KV head's rows
+    const int tb = b / a.upb;
+    const int id = live ? a.block_tables[(int64_t)s * a.MAXB + tb] : -1;
     const bool mapped = (unsigned)id < (unsigned)a.NB;   // ids outside the pool are never followed
     if (!mapped) ntok = 0;
     Window d;
-    d.slab = mapped ? id * Hkv + kvh : 0;
+    d.slab = mapped ? (id * Hkv + kvh) * a.upb + (b - tb * a.upb) : 0;
     const bool last = (b + 1 == nb) || ((b + 1) % bpp == 0) || (j + 1 == nshare);
     const bool seg_first = (b == 0) || (j == 0);
     d.meta = ntok | (last ? kMetaLast : 0) | (seg_first ? kMetaSegFirst : 0);

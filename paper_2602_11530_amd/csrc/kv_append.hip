@@ -12,7 +12,8 @@ constexpr int kAppendThreads = 256;
 __global__ __launch_bounds__(kAppendThreads) void kv_append_kernel(
     const u32x4* __restrict__ k_new, const u32x4* __restrict__ v_new, u32x4* __restrict__ k_pool,
     u32x4* __restrict__ v_pool, const int32_t* __restrict__ block_tables,
-    const int32_t* __restrict__ context_lens, int S, int Hkv, int MAXB, int max_ctx, int NB) {
+    const int32_t* __restrict__ context_lens, int S, int Hkv, int MAXB, int B, int max_ctx,
+    int NB) {
   constexpr int kRowChunks = kHeadDim * 2 / 16;   // 16-byte chunks per row
   const int64_t idx = (int64_t)blockIdx.x * kAppendThreads + threadIdx.x;   // (s, kvh, chunk)
   const int64_t total = (int64_t)S * Hkv * kRowChunks;
@@ -23,9 +24,9 @@ __global__ __launch_bounds__(kAppendThreads) void kv_append_kernel(
   const int L = min(max(context_lens[s], 0), max_ctx);
   if (L <= 0) return;
   const int t = L - 1;
-  const int id = block_tables[(int64_t)s * MAXB + t / kBlockTokens];
+  const int id = block_tables[(int64_t)s * MAXB + t / B];
   if ((unsigned)id >= (unsigned)NB) return;   // never follow a corrupt id
-  const int64_t dst = (((int64_t)id * Hkv + kvh) * kBlockTokens + t % kBlockTokens) * kRowChunks + chunk;
+  const int64_t dst = (((int64_t)id * Hkv + kvh) * B + t % B) * kRowChunks + chunk;
   k_pool[dst] = k_new[idx];
   v_pool[dst] = v_new[idx];
 }
@@ -34,13 +35,13 @@ __global__ __launch_bounds__(kAppendThreads) void kv_append_kernel(
 
 hipError_t launch_kv_append(const uint16_t* k_new, const uint16_t* v_new, uint16_t* k_pool,
                             uint16_t* v_pool, const int32_t* block_tables,
-                            const int32_t* context_lens, int S, int Hkv, int MAXB, int max_ctx,
-                            int NB, hipStream_t stream) {
+                            const int32_t* context_lens, int S, int Hkv, int MAXB, int B,
+                            int max_ctx, int NB, hipStream_t stream) {
   const int64_t total = (int64_t)S * Hkv * (kHeadDim * 2 / 16);
   dim3 grid((unsigned)((total + kAppendThreads - 1) / kAppendThreads));
   hipLaunchKernelGGL(kv_append_kernel, grid, dim3(kAppendThreads), 0, stream, (const u32x4*)k_new,
                      (const u32x4*)v_new, (u32x4*)k_pool, (u32x4*)v_pool, block_tables,
-                     context_lens, S, Hkv, MAXB, max_ctx, NB);
+                     context_lens, S, Hkv, MAXB, B, max_ctx, NB);
   return hipGetLastError();
 }
 

@@ -24,21 +24,24 @@ int check_shape(const pkv_attn_shape* sh, Geometry* g) {
   if (!sh) return PKV_ERR_NULL;
   if (sh->num_seqs < 0 || sh->num_seqs > pkv::kMaxSeqs) return PKV_ERR_SHAPE;
   if (sh->num_q_heads <= 0 || sh->num_kv_heads <= 0) return PKV_ERR_SHAPE;
-  if (sh->head_dim != pkv::kHeadDim || sh->block_size != pkv::kBlockTokens) return PKV_ERR_SHAPE;
+  if (sh->head_dim != pkv::kHeadDim) return PKV_ERR_SHAPE;
+  const int B = sh->block_size;
+  if (B != 16 && B != 32 && B != pkv::kMaxBlockSize) return PKV_ERR_SHAPE;
   if (sh->num_q_heads % sh->num_kv_heads != 0) return PKV_ERR_SHAPE;
   const int G = sh->num_q_heads / sh->num_kv_heads;
   if (G > pkv::kMaxGroup) return PKV_ERR_SHAPE;
   if (sh->max_blocks_per_seq <= 0) return PKV_ERR_SHAPE;
-  if ((int64_t)sh->max_blocks_per_seq * pkv::kBlockTokens > INT32_MAX) return PKV_ERR_SHAPE;
-  const int cap = sh->max_blocks_per_seq * pkv::kBlockTokens;
+  if ((int64_t)sh->max_blocks_per_seq * B > INT32_MAX) return PKV_ERR_SHAPE;
+  const int cap = sh->max_blocks_per_seq * B;
   if (sh->max_context_len < 0 || sh->max_context_len > cap) return PKV_ERR_SHAPE;
   const int max_ctx = sh->max_context_len ? sh->max_context_len : cap;
   int P = sh->partition_size;
   if (P < 0) return PKV_ERR_SHAPE;
   if (P == 0) P = kDefaultPartition;
-  if (P % pkv::kBlockTokens != 0 || P < pkv::kBlockTokens || P > pkv::kMaxPartition)
-    return PKV_ERR_SHAPE;
-  if (sh->num_pool_blocks < 1 || sh->num_pool_blocks * sh->num_kv_heads > INT32_MAX)
+  if (P % B != 0 || P < B || P > pkv::kMaxPartition) return PKV_ERR_SHAPE;
+  // 4 KiB slabs (16 tokens of one KV head) are numbered in 32 bits on the device
+  if (sh->num_pool_blocks < 1 ||
+      sh->num_pool_blocks * sh->num_kv_heads * (B / pkv::kBlockTokens) > INT32_MAX)
     return PKV_ERR_SHAPE;
   // stream positions, slots and rows are 32-bit on the device
   const int64_t max_blocks = (max_ctx + pkv::kBlockTokens - 1) / pkv::kBlockTokens;
@@ -137,6 +140,7 @@ static int prepare_attn(const int32_t* block_tables, const int32_t* context_lens
   a->Hkv = shape->num_kv_heads;
   a->G = g.G;
   a->MAXB = shape->max_blocks_per_seq;
+  a->upb = shape->block_size / pkv::kBlockTokens;
   a->P = g.P;
   a->max_ctx = g.max_ctx;
   a->NB = (int)shape->num_pool_blocks;
@@ -220,7 +224,7 @@ int kv_append(const void* k_new, const void* v_new, void* k_pool, void* v_pool,
   const hipError_t e = pkv::launch_kv_append(
       static_cast<const uint16_t*>(k_new), static_cast<const uint16_t*>(v_new),
       static_cast<uint16_t*>(k_pool), static_cast<uint16_t*>(v_pool), block_tables, context_lens,
-      shape->num_seqs, shape->num_kv_heads, shape->max_blocks_per_seq, g.max_ctx,
+      shape->num_seqs, shape->num_kv_heads, shape->max_blocks_per_seq, shape->block_size, g.max_ctx,
       (int)shape->num_pool_blocks, static_cast<hipStream_t>(stream));
   return launch_status(e);
 }

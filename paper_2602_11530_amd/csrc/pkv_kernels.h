@@ -10,7 +10,9 @@ namespace pkv {
 typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));  // one 16-byte lane load
 
 constexpr int kHeadDim = 128;        // D
-constexpr int kBlockTokens = 16;     // B
+constexpr int kBlockTokens = 16;     // tokens per streaming unit (one MFMA tile of keys); a physical
+                                     // block of B = 16, 32 or 64 tokens holds B/16 units per KV head
+constexpr int kMaxBlockSize = 64;
 constexpr int kMaxPartition = 65536; // tokens covered by one partial result, upper bound
 constexpr int kMaxGroup = 16;        // query heads per KV head
 constexpr int kMaxSeqs = 2048;       // per-request prefix arrays live in LDS
@@ -26,7 +28,8 @@ constexpr int kStreamGroups = PKV_STREAM_GROUPS;
 constexpr int kStreamWaves = kStreamGroups * kStreamWavesPerGroup;
 
 // How the batch's KV blocks are laid out as one stream and cut into shares.
-//   Segment (s, kvh) holds the nblk_s = ceil(L_s/16) blocks of request s for KV
+//   Segment (s, kvh) holds the nblk_s = ceil(L_s/16) 16-token units ("blocks" below;
+//   a physical block of B tokens is B/16 of them in a row) of request s for KV
 //   head kvh; segments follow each other in (s, kvh) order; position pos of the
 //   stream is block b of segment (s, kvh) with
 //       pos = Hkv * cumB[s] + kvh * nblk_s + b,     cumB[s] = sum_{s'<s} nblk_s'.
@@ -58,6 +61,7 @@ struct AttnLaunch {
   int32_t* ws_cum; // [2 * (S + 1)]   cumB then cumNP, written by the stream pass for the merge
   float scale_log2e;
   int S, Hq, Hkv, G, MAXB;
+  int upb;         // 16-token units per physical block (B / 16)
   int P;           // partition size, tokens
   int max_ctx;     // context lengths are clamped to [0, max_ctx] (<= MAXB * 16)
   int NB;          // physical blocks per pool; ids outside [0, NB) are never followed
@@ -77,7 +81,7 @@ hipError_t launch_kv_block_copy(const void* src, void* dst, const int32_t* block
 // New token's K and V rows into slot context_lens[s] - 1 of every request.
 hipError_t launch_kv_append(const uint16_t* k_new, const uint16_t* v_new, uint16_t* k_pool,
                             uint16_t* v_pool, const int32_t* block_tables,
-                            const int32_t* context_lens, int S, int Hkv, int MAXB, int max_ctx,
-                            int NB, hipStream_t stream);
+                            const int32_t* context_lens, int S, int Hkv, int MAXB, int B,
+                            int max_ctx, int NB, hipStream_t stream);
 
 }  // namespace pkv

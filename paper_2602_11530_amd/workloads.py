@@ -151,15 +151,16 @@ def make_tables(lens, num_pool_blocks: int, rng: np.random.Generator,
 
 def custom(lens, num_q_heads: int, num_kv_heads: int, seed: int,
            num_pool_blocks: Optional[int] = None, maxb: Optional[int] = None,
-           partition_size: int = 0, name: str = "custom", fill: int = -1) -> Workload:
-    """Arbitrary lengths (edge-case sweeps)."""
+           partition_size: int = 0, name: str = "custom", fill: int = -1,
+           block_size: int = BLOCK_SIZE) -> Workload:
+    """Arbitrary lengths (edge-case sweeps), any block size."""
     lens = np.asarray(lens, dtype=np.int32)
-    need = int(((lens.astype(np.int64) + BLOCK_SIZE - 1) // BLOCK_SIZE).sum())
+    need = int(((lens.astype(np.int64) + block_size - 1) // block_size).sum())
     nb = max(need, 1) if num_pool_blocks is None else num_pool_blocks
     rng = np.random.default_rng(seed)
-    tables = make_tables(lens, nb, rng, maxb=maxb, fill=fill)
+    tables = make_tables(lens, nb, rng, block_size=block_size, maxb=maxb, fill=fill)
     return Workload(name, num_q_heads, num_kv_heads, lens, tables, nb,
-                    partition_size=partition_size, seed=seed)
+                    partition_size=partition_size, block_size=block_size, seed=seed)
 
 
 def cfg1_tiny(seed: int = BASE_SEED + 1) -> Workload:
@@ -263,7 +264,7 @@ def subset(w: Workload, idx) -> Workload:
                     np.ascontiguousarray(w.context_lens[idx]),
                     np.ascontiguousarray(w.block_tables[idx]),
                     w.num_pool_blocks, num_layers=w.num_layers,
-                    partition_size=w.partition_size, seed=w.seed,
+                    partition_size=w.partition_size, block_size=w.block_size, seed=w.seed,
                     phase=None if w.phase is None else w.phase[idx])
 
 
