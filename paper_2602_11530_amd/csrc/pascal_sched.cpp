@@ -117,7 +117,10 @@ struct pascal_sched {
   }
 
   // ---- order bookkeeping -----------------------------------------------------------------
-  static void remove_from(std::vector<int>& q, int rid) { q.erase(std::find(q.begin(), q.end(), rid)); }
+  static void remove_from(std::vector<int>& q, int rid) {
+    const auto it = std::find(q.begin(), q.end(), rid);
+    if (it != q.end()) q.erase(it);
+  }
 
   void push_op(Instance& at, int kind, int instance, int rid, const std::vector<int32_t>& blocks,
                int other = -1, const std::vector<int32_t>* other_blocks = nullptr) {
@@ -151,22 +154,25 @@ struct pascal_sched {
     std::vector<int> order(ins.queue[0]);
     order.insert(order.end(), ins.queue[1].begin(), ins.queue[1].end());
     std::vector<char> evicted_now(order.size(), 0);
+    // blocks held by resident requests behind the current position: what evictions could free
+    int64_t resident_behind = 0;
+    for (int rid : order)
+      if (req[rid].state == PASCAL_RESIDENT) resident_behind += (int64_t)req[rid].blocks.size();
     for (size_t pos = 0; pos < order.size(); ++pos) {
-      if (evicted_now[pos]) continue;
       const int rid = order[pos];
       Request& q = req[rid];
+      if (q.state == PASCAL_RESIDENT) resident_behind -= (int64_t)q.blocks.size();
+      if (evicted_now[pos]) continue;
       const int after = q.state == PASCAL_QUEUED ? q.prompt : q.kv_tokens + 1;
       const int extra = blocks_for(after) - (int)q.blocks.size();
       // evict only when that makes the request fit
-      int64_t reclaimable = (int64_t)ins.free_blocks.size();
-      for (size_t b = pos + 1; b < order.size(); ++b)
-        if (req[order[b]].state == PASCAL_RESIDENT) reclaimable += (int64_t)req[order[b]].blocks.size();
-      if (extra > reclaimable) continue;
+      if (extra > (int64_t)ins.free_blocks.size() + resident_behind) continue;
       for (size_t b = order.size(); extra > (int)ins.free_blocks.size() && b-- > pos + 1;) {
         Request& v = req[order[b]];
         if (v.state != PASCAL_RESIDENT) continue;
         push_op(ins, PASCAL_OP_OFFLOAD, i, order[b], v.blocks);
         ins.free_blocks.insert(ins.free_blocks.end(), v.blocks.begin(), v.blocks.end());
+        resident_behind -= (int64_t)v.blocks.size();
         v.host_blocks = (int)v.blocks.size();
         v.blocks.clear();
         v.state = PASCAL_OFFLOADED;
