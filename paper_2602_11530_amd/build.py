@@ -1,4 +1,5 @@
-"""Builds libpkv.so (gfx950, hipcc) and libpascal_sched.so (host only, g++) in-tree.
+"""Builds libpkv.so (gfx950, hipcc), libpascal_sched.so (host only, g++) and the native
+driver program serve_trace in-tree.
 ``python -m paper_2602_11530_amd.build``."""
 from __future__ import annotations
 
@@ -47,11 +48,22 @@ def build_sched(verbose: bool = True) -> str:
                     SCHED_LIB, verbose)
 
 
+DRIVER = os.path.join(PKG, "serve_trace")
+
+
+def build_driver(verbose: bool = True) -> str:
+    """The native driver program (host code only): links against both libraries."""
+    return _compile([HIPCC, "-O2", "-std=c++17", "-Wall", os.path.join(CSRC, "serve_trace.cpp"),
+                     "-L", PKG, "-lpkv", "-lpascal_sched", "-Wl,-rpath,$ORIGIN"], DRIVER, verbose)
+
+
 def build(verbose: bool = True, extra_flags=()) -> str:
-    """Compile every source of both libraries; always recompiles (seconds)."""
+    """Compile every source of both libraries and the driver; always recompiles (seconds)."""
     build_sched(verbose)
-    return _compile([HIPCC, *FLAGS, *extra_flags] + [os.path.join(CSRC, s) for s in SOURCES],
-                    LIB, verbose)
+    lib = _compile([HIPCC, *FLAGS, *extra_flags] + [os.path.join(CSRC, s) for s in SOURCES],
+                   LIB, verbose)
+    build_driver(verbose)
+    return lib
 
 
 if __name__ == "__main__":
