@@ -5,7 +5,7 @@
  *
  * C ABI, host memory only: no pointer here is device memory and no call
  * touches the GPU.  The caller executes the returned data-movement orders with
- * kv_blocks_offload / kv_blocks_reload / kv_blocks_gather / kv_blocks_scatter
+ * kv_blocks_offload / kv_blocks_reload / kv_blocks_move (or gather + scatter)
  * and runs the batch with kv_append + paged_decode_attn(_layers).
  *
  * Model (paper Section IV).  A cluster of instances, each with its own pool of

@@ -162,6 +162,24 @@ int kv_blocks_scatter(const void* staging, void* pool, const int32_t* block_ids,
                       void* stream);
 
 /*
+ * dst_pool[dst_ids[i]] = src_pool[src_ids[i]]: migration of a request's KV cache
+ * between two instances whose pools live on the same GPU (Section IV-B moves the
+ * entire KV cache at the phase transition; an MI355X holds the pools of several
+ * instances of a 32B model), in one pass without a staging image: each byte is
+ * read once and written once, half the traffic of gather followed by scatter.
+ * The two pools may be one and the same only if no block is both read and
+ * written (unchecked); dst ids must be distinct.  An entry whose source or
+ * destination id is out of range is skipped.
+ *
+ *   src_pool, dst_pool  device, src_pool_blocks / dst_pool_blocks blocks of
+ *                       block_bytes bytes
+ *   src_ids, dst_ids    device int32 [n_blocks]
+ */
+int kv_blocks_move(const void* src_pool, const int32_t* src_ids, void* dst_pool,
+                   const int32_t* dst_ids, int64_t n_blocks, int64_t block_bytes,
+                   int64_t src_pool_blocks, int64_t dst_pool_blocks, void* stream);
+
+/*
  * Eviction of a preempted request to the backing store: the listed blocks are
  * gathered into `staging` and that image is copied to page-locked host memory,
  * both on `stream` (paper Section II-B: a preempted request's KV cache is

@@ -46,6 +46,8 @@ def _load() -> ctypes.CDLL:
         lib.pkv_oracle_kv_blocks_gather.restype = ctypes.c_int
         lib.pkv_oracle_kv_blocks_scatter.argtypes = [p, p, p, i64, i64, i64]
         lib.pkv_oracle_kv_blocks_scatter.restype = ctypes.c_int
+        lib.pkv_oracle_kv_blocks_move.argtypes = [p, p, p, p, i64, i64, i64, i64]
+        lib.pkv_oracle_kv_blocks_move.restype = ctypes.c_int
         lib.pkv_oracle_max_threads.restype = ctypes.c_int
         lib.pkv_oracle_kv_append.argtypes = [p, p, p, p, p, p, i64, i64, i64, i64, i64, i64]
         lib.pkv_oracle_kv_append.restype = ctypes.c_int
@@ -120,6 +122,25 @@ def kv_blocks_scatter(staging: np.ndarray, pool: np.ndarray, block_ids) -> np.nd
         raise ValueError("staging size does not match the id list")
     rc = _load().pkv_oracle_kv_blocks_scatter(staging.ctypes.data, out.ctypes.data,
                                               ids.ctypes.data, len(ids), bb, NB)
+    if rc != 0:
+        raise ValueError(f"oracle rejected its input (code {rc})")
+    return out
+
+
+def kv_blocks_move(src_pool: np.ndarray, src_ids, dst_pool: np.ndarray, dst_ids) -> np.ndarray:
+    """A copy of ``dst_pool`` with page dst_ids[i] replaced by page src_ids[i] of ``src_pool``."""
+    src = np.ascontiguousarray(src_pool)
+    out = np.array(dst_pool, copy=True, order="C")
+    a, b = _c(np.asarray(src_ids), np.int32), _c(np.asarray(dst_ids), np.int32)
+    if len(a) != len(b):
+        raise ValueError("the two id lists differ in length")
+    if len(a) == 0:
+        return out
+    bb = src.nbytes // src.shape[0]
+    if out.nbytes // out.shape[0] != bb:
+        raise ValueError("the pools' block sizes differ")
+    rc = _load().pkv_oracle_kv_blocks_move(src.ctypes.data, a.ctypes.data, out.ctypes.data,
+                                           b.ctypes.data, len(a), bb, src.shape[0], out.shape[0])
     if rc != 0:
         raise ValueError(f"oracle rejected its input (code {rc})")
     return out

@@ -26,6 +26,7 @@
  *   migration of a request's whole KV cache at the phase boundary
  *   (Section IV-B, "KV cache transfer overhead") move whole pages:
  *     gather : staging[i] = pool[ids[i]]     scatter : pool[ids[i]] = staging[i]
+ *     move   : dst[dst_ids[i]] = src[src_ids[i]]   (two pools on one device)
  *   bytewise, everything else untouched.
  *
  *   Before attention the decode step stores the new token's K and V rows at
@@ -145,6 +146,25 @@ int pkv_oracle_kv_blocks_scatter(const uint8_t* staging, uint8_t* pool, const in
   free(seen);
   for (int64_t i = 0; i < n; ++i)
     memcpy(pool + (int64_t)ids[i] * block_bytes, staging + i * block_bytes, (size_t)block_bytes);
+  return 0;
+}
+
+/* dst[dst_ids[i]] = src[src_ids[i]], whole pages; the two pools are distinct buffers here.
+ * A destination listed twice is an error (-4). */
+int pkv_oracle_kv_blocks_move(const uint8_t* src, const int32_t* src_ids, uint8_t* dst,
+                              const int32_t* dst_ids, int64_t n, int64_t block_bytes,
+                              int64_t src_NB, int64_t dst_NB) {
+  if (n < 0 || block_bytes <= 0) return -1;
+  uint8_t* seen = (uint8_t*)calloc((size_t)(dst_NB > 0 ? dst_NB : 1), 1);
+  if (!seen) return -3;
+  for (int64_t i = 0; i < n; ++i) {
+    if (src_ids[i] < 0 || src_ids[i] >= src_NB || dst_ids[i] < 0 || dst_ids[i] >= dst_NB) { free(seen); return -2; }
+    if (seen[dst_ids[i]]) { free(seen); return -4; }
+    seen[dst_ids[i]] = 1;
+  }
+  free(seen);
+  for (int64_t i = 0; i < n; ++i)
+    memcpy(dst + (int64_t)dst_ids[i] * block_bytes, src + (int64_t)src_ids[i] * block_bytes, (size_t)block_bytes);
   return 0;
 }
 

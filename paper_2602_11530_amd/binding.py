@@ -25,7 +25,7 @@ PKV_ERR_HOST = -6
 EXPORTS = (
     "pkv_attn_partition_size", "pkv_attn_workspace_bytes", "paged_decode_attn",
     "paged_decode_attn_layers",
-    "kv_blocks_gather", "kv_blocks_scatter", "kv_blocks_offload", "kv_blocks_reload",
+    "kv_blocks_gather", "kv_blocks_scatter", "kv_blocks_move", "kv_blocks_offload", "kv_blocks_reload",
     "kv_append", "pkv_status_string",
     "pkv_last_launch_error", "pkv_version",
 )
@@ -88,6 +88,8 @@ def lib() -> ctypes.CDLL:
         L.kv_blocks_gather.restype = ctypes.c_int
         L.kv_blocks_scatter.argtypes = [vp, vp, i32p, i64, i64, i64, vp]
         L.kv_blocks_scatter.restype = ctypes.c_int
+        L.kv_blocks_move.argtypes = [vp, i32p, vp, i32p, i64, i64, i64, i64, vp]
+        L.kv_blocks_move.restype = ctypes.c_int
         L.kv_blocks_offload.argtypes = [vp, i32p, vp, vp, i64, i64, i64, vp]
         L.kv_blocks_offload.restype = ctypes.c_int
         L.kv_blocks_reload.argtypes = [vp, vp, vp, i32p, i64, i64, i64, vp]
@@ -183,6 +185,14 @@ def kv_blocks_scatter(staging, pool, block_ids, n_blocks: int, block_bytes: int,
                       num_pool_blocks: int, stream=None) -> None:
     _check(lib().kv_blocks_scatter(_ptr(staging), _ptr(pool), _ptr(block_ids), n_blocks,
                                    block_bytes, num_pool_blocks, _stream(stream)))
+
+
+def kv_blocks_move(src_pool, src_ids, dst_pool, dst_ids, n_blocks: int, block_bytes: int,
+                   src_pool_blocks: int, dst_pool_blocks: int, stream=None) -> None:
+    """dst_pool[dst_ids[i]] = src_pool[src_ids[i]] in one pass (pools on the same GPU)."""
+    _check(lib().kv_blocks_move(_ptr(src_pool), _ptr(src_ids), _ptr(dst_pool), _ptr(dst_ids),
+                                n_blocks, block_bytes, src_pool_blocks, dst_pool_blocks,
+                                _stream(stream)))
 
 
 def kv_blocks_offload(pool, block_ids, staging, host_dst, n_blocks: int, block_bytes: int,

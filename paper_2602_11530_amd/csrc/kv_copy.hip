@@ -16,20 +16,9 @@ constexpr int kCopyThreads = 256;
 constexpr int kChunksPerThread = 8;                               // 16-byte chunks
 constexpr int kChunksPerGroup = kCopyThreads * kChunksPerThread;  // 32 KiB per workgroup
 
-// blockIdx.x = index into block_ids, blockIdx.y = 32 KiB slice of that block.
-// The physical id is wave-uniform, so the pool-side base address is scalar;
-// byte offsets are 64-bit (a pool passes 2 GiB at the long-context sizes).
-template <bool kGather>
-__global__ __launch_bounds__(kCopyThreads) void kv_block_copy_kernel(
-    const u32x4* __restrict__ src, u32x4* __restrict__ dst, const int32_t* __restrict__ block_ids,
-    int64_t chunks_per_block, int64_t num_pool_blocks) {
-  const int64_t i = blockIdx.x;
-  const int64_t phys = block_ids[i];
-  if (phys < 0 || phys >= num_pool_blocks) return;   // never follow a corrupt id
-  const int64_t pool_base = phys * chunks_per_block;
-  const int64_t stage_base = i * chunks_per_block;
-  const u32x4* s = src + (kGather ? pool_base : stage_base);
-  u32x4* d = dst + (kGather ? stage_base : pool_base);
+// One workgroup moves one 32 KiB slice: all loads first, then all stores.
+__device__ __forceinline__ void copy_slice(const u32x4* __restrict__ s, u32x4* __restrict__ d,
+                                           int64_t chunks_per_block) {
   const int64_t c0 = (int64_t)blockIdx.y * kChunksPerGroup + threadIdx.x;
   if (((int64_t)blockIdx.y + 1) * kChunksPerGroup <= chunks_per_block) {
     // Whole slice inside the block (always, for 32 KiB blocks): all loads are
@@ -48,6 +37,32 @@ __global__ __launch_bounds__(kCopyThreads) void kv_block_copy_kernel(
   }
 }
 
+// blockIdx.x = index into block_ids, blockIdx.y = 32 KiB slice of that block.
+// The physical id is wave-uniform, so the pool-side base address is scalar;
+// byte offsets are 64-bit (a pool passes 2 GiB at the long-context sizes).
+template <bool kGather>
+__global__ __launch_bounds__(kCopyThreads) void kv_block_copy_kernel(
+    const u32x4* __restrict__ src, u32x4* __restrict__ dst, const int32_t* __restrict__ block_ids,
+    int64_t chunks_per_block, int64_t num_pool_blocks) {
+  const int64_t i = blockIdx.x;
+  const int64_t phys = block_ids[i];
+  if (phys < 0 || phys >= num_pool_blocks) return;   // never follow a corrupt id
+  const int64_t pool_base = phys * chunks_per_block;
+  const int64_t stage_base = i * chunks_per_block;
+  copy_slice(src + (kGather ? pool_base : stage_base), dst + (kGather ? stage_base : pool_base),
+             chunks_per_block);
+}
+
+// Pool to pool: block src_ids[i] of one pool becomes block dst_ids[i] of another.
+__global__ __launch_bounds__(kCopyThreads) void kv_block_move_kernel(
+    const u32x4* __restrict__ src, const int32_t* __restrict__ src_ids, int64_t src_pool_blocks,
+    u32x4* __restrict__ dst, const int32_t* __restrict__ dst_ids, int64_t dst_pool_blocks,
+    int64_t chunks_per_block) {
+  const int64_t from = src_ids[blockIdx.x], to = dst_ids[blockIdx.x];
+  if (from < 0 || from >= src_pool_blocks || to < 0 || to >= dst_pool_blocks) return;
+  copy_slice(src + from * chunks_per_block, dst + to * chunks_per_block, chunks_per_block);
+}
+
 }  // namespace
 
 hipError_t launch_kv_block_copy(const void* src, void* dst, const int32_t* block_ids,
@@ -63,6 +78,17 @@ hipError_t launch_kv_block_copy(const void* src, void* dst, const int32_t* block
   else
     hipLaunchKernelGGL(kv_block_copy_kernel<false>, grid, dim3(kCopyThreads), 0, stream,
                        (const u32x4*)src, (u32x4*)dst, block_ids, chunks, num_pool_blocks);
+  return hipGetLastError();
+}
+
+hipError_t launch_kv_block_move(const void* src, const int32_t* src_ids, int64_t src_pool_blocks,
+                                void* dst, const int32_t* dst_ids, int64_t dst_pool_blocks,
+                                int64_t n_blocks, int64_t block_bytes, hipStream_t stream) {
+  const int64_t chunks = block_bytes / 16;
+  const int64_t slices = (chunks + kChunksPerGroup - 1) / kChunksPerGroup;
+  dim3 grid((unsigned)n_blocks, (unsigned)slices, 1);
+  hipLaunchKernelGGL(kv_block_move_kernel, grid, dim3(kCopyThreads), 0, stream, (const u32x4*)src,
+                     src_ids, src_pool_blocks, (u32x4*)dst, dst_ids, dst_pool_blocks, chunks);
   return hipGetLastError();
 }
 

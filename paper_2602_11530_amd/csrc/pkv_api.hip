@@ -280,6 +280,22 @@ int kv_blocks_scatter(const void* staging, void* pool, const int32_t* block_ids,
   return copy_call(pool, staging, block_ids, n_blocks, block_bytes, num_pool_blocks, false, stream);
 }
 
+int kv_blocks_move(const void* src_pool, const int32_t* src_ids, void* dst_pool,
+                   const int32_t* dst_ids, int64_t n_blocks, int64_t block_bytes,
+                   int64_t src_pool_blocks, int64_t dst_pool_blocks, void* stream) {
+  if (n_blocks < 0 || block_bytes <= 0 || src_pool_blocks < 0 || dst_pool_blocks < 0) return PKV_ERR_SHAPE;
+  if (block_bytes % 16 != 0) return PKV_ERR_ALIGN;
+  if (n_blocks > INT32_MAX || block_bytes > ((int64_t)1 << 30)) return PKV_ERR_SHAPE;
+  if (n_blocks == 0) return PKV_OK;
+  if (!src_pool || !dst_pool || !src_ids || !dst_ids) return PKV_ERR_NULL;
+  if (misaligned16(src_pool) || misaligned16(dst_pool) || (reinterpret_cast<uintptr_t>(src_ids) & 3u) ||
+      (reinterpret_cast<uintptr_t>(dst_ids) & 3u))
+    return PKV_ERR_ALIGN;
+  return launch_status(pkv::launch_kv_block_move(src_pool, src_ids, src_pool_blocks, dst_pool, dst_ids,
+                                                 dst_pool_blocks, n_blocks, block_bytes,
+                                                 static_cast<hipStream_t>(stream)));
+}
+
 int kv_blocks_offload(const void* pool, const int32_t* block_ids, void* staging, void* host_dst,
                       int64_t n_blocks, int64_t block_bytes, int64_t num_pool_blocks, void* stream) {
   bool empty = false;

@@ -78,6 +78,11 @@ hipError_t launch_kv_block_copy(const void* src, void* dst, const int32_t* block
                                 int64_t n_blocks, int64_t block_bytes, int64_t num_pool_blocks,
                                 bool gather, hipStream_t stream);
 
+// Pool to pool: dst[dst_ids[i]] = src[src_ids[i]], no staging image in between.
+hipError_t launch_kv_block_move(const void* src, const int32_t* src_ids, int64_t src_pool_blocks,
+                                void* dst, const int32_t* dst_ids, int64_t dst_pool_blocks,
+                                int64_t n_blocks, int64_t block_bytes, hipStream_t stream);
+
 // New token's K and V rows into slot context_lens[s] - 1 of every request.
 hipError_t launch_kv_append(const uint16_t* k_new, const uint16_t* v_new, uint16_t* k_pool,
                             uint16_t* v_pool, const int32_t* block_tables,

@@ -262,11 +262,9 @@ struct Server {
           upload_ids(ids, n, ids_d, 0);
           upload_ids(ids + n, n, ids2_d, 1);
           for (int l = 0; l < o.layers; ++l)
-            for (int v = 0; v < 2; ++v) {
-              PKV_OK_(kv_blocks_gather(pool(v, op.instance, l), ids_d, staging, n, kBlockBytes, o.blocks, stream));
-              PKV_OK_(kv_blocks_scatter(staging, pool(v, op.other_instance, l), ids2_d, n, kBlockBytes, o.blocks,
-                                        stream));
-            }
+            for (int v = 0; v < 2; ++v)
+              PKV_OK_(kv_blocks_move(pool(v, op.instance, l), ids_d, pool(v, op.other_instance, l), ids2_d, n,
+                                     kBlockBytes, o.blocks, o.blocks, stream));
           HIP_OK(hipStreamSynchronize(stream));
           verify(op.other_instance, op.request, ids + n, n, "after migration");
           poison(op.instance, ids, n);

@@ -196,3 +196,17 @@ int main(void) {
                            "-Wl,-rpath,/opt/rocm/lib", "-L/opt/rocm/lib"])
     out = subprocess.check_output([str(exe)]).decode().split()
     assert int(out[0]) >= 1000 and out[1] == "ok"
+
+
+def test_move_argument_errors_before_launch():
+    L = pkv.lib()
+    f = lambda sp, si, dp, di, n, bb=32768, a=64, b=64: L.kv_blocks_move(sp, si, dp, di, n, bb, a, b, None)
+    assert f(None, None, None, None, 0) == pkv.PKV_OK
+    assert f(16, 16, 32, 16, -1) == pkv.PKV_ERR_SHAPE
+    assert f(16, 16, 32, 16, 4, bb=0) == pkv.PKV_ERR_SHAPE
+    assert f(16, 16, 32, 16, 4, a=-1) == pkv.PKV_ERR_SHAPE
+    assert f(16, 16, 32, 16, 4, bb=40) == pkv.PKV_ERR_ALIGN
+    assert f(None, 16, 32, 16, 4) == pkv.PKV_ERR_NULL
+    assert f(16, 16, 32, None, 4) == pkv.PKV_ERR_NULL
+    assert f(16, 16, 24, 16, 4) == pkv.PKV_ERR_ALIGN
+    assert f(16, 18, 32, 16, 4) == pkv.PKV_ERR_ALIGN

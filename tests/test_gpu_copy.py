@@ -109,3 +109,73 @@ def test_out_of_range_ids_are_skipped(device):
     want = np.zeros_like(pool)
     want[ids[ok]] = pool[ids[ok]]
     assert np.array_equal(to_bits(dst), want)
+
+
+@pytest.mark.parametrize("hkv,n", [(8, 37), (2, 5), (1, 1), (8, 700)])
+def test_move_bit_exact(device, hkv, n):
+    """Pool to pool in one pass equals the oracle's move, and gather + scatter."""
+    rng = np.random.default_rng(300 + n)
+    NBs, NBd = max(2 * n, 8), max(3 * n, 5)
+    src = rng.integers(0, 65536, size=(NBs, hkv, 16, 128)).astype(np.uint16)
+    dst = rng.integers(0, 65536, size=(NBd, hkv, 16, 128)).astype(np.uint16)
+    bb = hkv * 16 * 128 * 2
+    a = rng.permutation(NBs)[:n].astype(np.int32)
+    b = rng.permutation(NBd)[:n].astype(np.int32)
+    src_d, dst_d = to_dev(src), to_dev(dst)
+    pkv.kv_blocks_move(src_d, to_dev(a), dst_d, to_dev(b), n, bb, NBs, NBd)
+    torch.cuda.synchronize()
+    assert np.array_equal(to_bits(dst_d), oracle.kv_blocks_move(src, a, dst, b))
+    assert np.array_equal(to_bits(src_d), src), "the source pool must not change"
+    # out-of-range entries on either side are skipped, the rest still moves
+    a2, b2 = a.copy(), b.copy()
+    a2[0] = NBs + 3
+    if n > 1:
+        b2[-1] = -1
+    dst_d = to_dev(dst)
+    pkv.kv_blocks_move(src_d, to_dev(a2), dst_d, to_dev(b2), n, bb, NBs, NBd)
+    torch.cuda.synchronize()
+    keep = np.ones(n, bool)
+    keep[0] = False
+    if n > 1:
+        keep[-1] = False
+    assert np.array_equal(to_bits(dst_d), oracle.kv_blocks_move(src, a[keep], dst, b[keep]))
+
+
+def test_move_within_one_pool_and_timing(device):
+    """Disjoint source and destination blocks of the same pool (cfg5's size: the KV of 24 of
+    96 requests, one layer's K pool); time against gather + scatter through staging."""
+    w = wl.cfg4_phase_mixed(num_layers=1)
+    mig = wl.make_migration(w, 0.25)
+    n, bb = len(mig.old_ids), w.block_bytes
+    NB = w.num_pool_blocks + n                      # the batch's blocks plus as many spare ones
+    rng = np.random.default_rng(5)
+    old = mig.old_ids.astype(np.int32)
+    new = (w.num_pool_blocks + rng.permutation(n)).astype(np.int32)
+    g = torch.Generator(device=device); g.manual_seed(3)
+    pool = torch.randint(-32768, 32767, (NB,) + tuple(w.pool_shape()[1:]), generator=g, device=device,
+                         dtype=torch.int16)
+    before = pool.clone()
+    old_d, new_d = to_dev(old), to_dev(new)
+    staging = torch.empty((n,) + tuple(w.pool_shape()[1:]), dtype=torch.int16, device=device)
+
+    def timed(fn, reps=20):
+        fn(); torch.cuda.synchronize()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        for _ in range(reps):
+            fn()
+        e1.record(); torch.cuda.synchronize()
+        return e0.elapsed_time(e1) / reps
+
+    ms_move = timed(lambda: pkv.kv_blocks_move(pool, old_d, pool, new_d, n, bb, NB, NB))
+    assert torch.equal(pool.index_select(0, new_d.long()), before.index_select(0, old_d.long()))
+    untouched = torch.from_numpy(np.setdiff1d(np.arange(NB), new)).to(device)
+    assert torch.equal(pool.index_select(0, untouched), before.index_select(0, untouched))
+
+    def two_step():
+        pkv.kv_blocks_gather(pool, old_d, staging, n, bb, NB)
+        pkv.kv_blocks_scatter(staging, pool, new_d, n, bb, NB)
+    ms_two = timed(two_step)
+    print(f"{n} blocks ({n * bb / 1e6:.0f} MB): move {ms_move * 1e3:.1f} us = {2 * n * bb / ms_move / 1e6:.0f} GB/s "
+          f"read+write; gather + scatter {ms_two * 1e3:.1f} us", flush=True)
+    assert ms_move < ms_two

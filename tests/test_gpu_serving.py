@@ -2,7 +2,7 @@
 (two sets of per-layer KV pools on the one GPU).  Every order the scheduler issues is
 executed through the C ABI — prefill installs, kv_append + paged_decode_attn per
 iteration, preemption through kv_blocks_offload / kv_blocks_reload, phase-transition
-migration through kv_blocks_gather / kv_blocks_scatter between the instances' pools.
+migration through kv_blocks_move between the instances' pools.
 
 A host mirror keeps what each request's K and V rows must be, independent of where
 they live; attention is compared with the oracle run on the mirror, and a request's
@@ -118,8 +118,7 @@ class Engine:
                 src, dst = self.ids(blocks), self.ids(other_blocks)
                 for l in range(self.L):
                     for a, b in ((self.k[inst][l], self.k[other][l]), (self.v[inst][l], self.v[other][l])):
-                        pkv.kv_blocks_gather(a, src, self.staging, n, self.bb, self.NB)
-                        pkv.kv_blocks_scatter(self.staging, b, dst, n, self.bb, self.NB)
+                        pkv.kv_blocks_move(a, src, b, dst, n, self.bb, self.NB, self.NB)
                 self.check_blocks(other, rid, other_blocks)
                 self.poison(inst, blocks)
             elif kind == sb.OP_FREE:

@@ -254,6 +254,25 @@ def test_gather_scatter_against_fancy_indexing():
         oracle.kv_blocks_gather(pool, np.array([50], np.int32))
 
 
+def test_move_against_fancy_indexing():
+    rng = np.random.default_rng(14)
+    src = rng.integers(0, 65536, size=(40, 2, 16, 128)).astype(np.uint16)
+    dst = rng.integers(0, 65536, size=(25, 2, 16, 128)).astype(np.uint16)
+    a = rng.permutation(40)[:11].astype(np.int32)
+    b = rng.permutation(25)[:11].astype(np.int32)
+    out = oracle.kv_blocks_move(src, a, dst, b)
+    want = dst.copy()
+    want[b] = src[a]
+    assert np.array_equal(out, want) and (out != dst).any()
+    # the same as a gather followed by a scatter
+    assert np.array_equal(out, oracle.kv_blocks_scatter(oracle.kv_blocks_gather(src, a), dst, b))
+    assert np.array_equal(oracle.kv_blocks_move(src, a[:0], dst, b[:0]), dst)
+    with pytest.raises(ValueError):
+        oracle.kv_blocks_move(src, a, dst, np.array([3] * 11, np.int32))     # a destination twice
+    with pytest.raises(ValueError):
+        oracle.kv_blocks_move(src, np.array([40], np.int32), dst, b[:1])     # source out of range
+
+
 def test_migration_round_trip_keeps_attention():
     w = wl.cfg1_tiny()
     q, k, v = wl.make_host_tensors(w)
