@@ -242,3 +242,35 @@ def test_reasoning_is_never_evicted_for_answering():
     assert c.req[a].phase == po.ANSWERING and c.req[b].phase == po.REASONING
     assert c.req[a].preemptions > 0, "the scenario should put the answering request under pressure"
     assert (po.LOW, po.ANSWERING) in evicted_levels
+
+
+@pytest.mark.parametrize("seed", range(25))
+def test_invariants_on_random_walks(seed):
+    """The same invariants under arbitrary interleavings and randomly drawn token kinds."""
+    rng = np.random.default_rng(2000 + seed)
+    n_inst = int(rng.integers(1, 4))
+    cfg = po.Config(num_instances=n_inst, gpu_blocks=int(rng.integers(6, 30)),
+                    block_tokens=int(rng.choice([1, 4, 16])), quantum=int(rng.integers(1, 10)),
+                    demote_tokens=int(rng.integers(8, 120)), headroom_blocks=int(rng.integers(0, 3)),
+                    tpot=0.05, max_batch=int(rng.choice([0, 2])))
+    c = Checked(cfg)
+    cap = cfg.gpu_blocks * cfg.block_tokens
+    now, live = 0.0, 0
+    for _ in range(300):
+        now += float(rng.exponential(0.03))
+        if live < 10 and rng.random() < 0.3:
+            c.submit(int(rng.integers(1, max(2, cap // 3))), now)
+            live += 1
+        i = int(rng.integers(0, n_inst))
+        rids, lens, _ = c.plan(i)
+        kinds = []
+        for rid, L in zip(rids, lens):
+            u = rng.random()
+            if L + 1 >= cap or u < 0.03:
+                kinds.append(po.END_OF_SEQUENCE)
+                live -= 1
+            elif c.req[rid].phase == po.REASONING and u < 0.10:
+                kinds.append(po.END_OF_REASONING)
+            else:
+                kinds.append(po.TOKEN)
+        c.commit(i, now, kinds)

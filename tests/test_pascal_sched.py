@@ -148,3 +148,47 @@ def test_library_equals_oracle_on_traces(kw, n_requests, rate):
         assert info.ttft == both.ref.ttft(rid)
         assert info.qoe == pytest.approx(both.ref.qoe(rid), rel=1e-12, abs=0)
         assert both.lib.request_blocks(rid) == []
+
+
+@pytest.mark.parametrize("seed", range(40))
+def test_library_equals_oracle_on_random_walks(seed):
+    """Arbitrary interleavings of arrivals and iterations, token kinds drawn at random (so
+    phase changes and completions hit every queue state), tiny pools, every knob varied."""
+    rng = np.random.default_rng(1000 + seed)
+    n_inst = int(rng.integers(1, 5))
+    kw = dict(num_instances=n_inst, gpu_blocks=int(rng.integers(6, 40)), block_tokens=int(rng.choice([1, 4, 16])),
+              quantum=int(rng.integers(1, 12)), demote_tokens=int(rng.integers(8, 200)),
+              headroom_blocks=int(rng.integers(0, 4)), tpot=float(rng.choice([0.01, 0.05, 0.3])),
+              max_batch=int(rng.choice([0, 0, 1, 3])))
+    both = Both(**kw)
+    cap_tokens = kw["gpu_blocks"] * kw["block_tokens"]
+    now, live = 0.0, 0
+    for step in range(400):
+        now += float(rng.exponential(0.03))
+        if live < 12 and rng.random() < 0.25:
+            both.submit(int(rng.integers(1, max(2, cap_tokens // 3))), now)
+            live += 1
+        i = int(rng.integers(0, n_inst))
+        rids, lens, _ = both.plan(i)
+        kinds = []
+        for rid, L in zip(rids, lens):
+            q = both.ref.req[rid]
+            u = rng.random()
+            if L + 1 >= cap_tokens or u < 0.03:         # must stop before it outgrows the pool
+                kinds.append(sb.END_OF_SEQUENCE)
+                live -= 1
+            elif q.phase == po.REASONING and u < 0.10:
+                kinds.append(sb.END_OF_REASONING)
+            else:
+                kinds.append(sb.TOKEN)
+        both.commit(i, now, kinds)
+        for j in range(n_inst):
+            assert both.lib.signals(j, now) == (both.ref.t(j, now), both.ref.m(j), both.ref.r(j),
+                                                both.ref.a(j), both.ref.free_blocks(j))
+    for rid, q in enumerate(both.ref.req):
+        info = both.lib.request(rid)
+        assert (info.state, info.phase, info.level, info.instance, info.kv_tokens, info.n_blocks,
+                info.preemptions, info.migrations) == \
+               (q.state, q.phase, q.level, q.instance, q.kv_tokens, len(q.blocks), q.preemptions, q.migrations)
+        assert both.lib.request_blocks(rid) == q.blocks
+        assert info.qoe == pytest.approx(both.ref.qoe(rid), rel=1e-12)
