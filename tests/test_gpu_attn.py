@@ -263,3 +263,25 @@ def test_random_shapes(device, case):
     check(w, q, k, v, got, f"case {case}: S={len(lens)} hq={hq} hkv={hkv} P={P} tokens={int(lens.sum())}")
     for s in np.nonzero(lens == 0)[0]:
         assert not got.reshape(w.q_shape())[s].any()
+
+
+@pytest.mark.parametrize("hq,hkv", [(8, 2), (16, 1)])
+def test_maximum_batch(device, hq, hkv):
+    """2048 requests in one call (the most the library takes): the per-request prefix arrays
+    fill the LDS budget and leave room for a single parked record at G = 16."""
+    rng = np.random.default_rng(77 + hq)
+    lens = rng.integers(0, 120, size=2048)
+    lens[[0, 5, 2047]] = [0, 1, 119]
+    w = wl.custom(lens, hq, hkv, seed=880 + hq, partition_size=int(rng.choice([0, 32])))
+    q, k, v = wl.make_host_tensors(w, poison_unused=True)
+    got = run_attn(w, q, k, v)
+    check(w, q, k, v, got, f"S=2048 hq={hq} hkv={hkv}")
+    for s in np.nonzero(lens == 0)[0][:5]:
+        assert not got.reshape(w.q_shape())[s].any()
+
+
+def test_one_very_long_request(device):
+    """131 072 tokens in one request (two partitions of the largest size), next to short ones."""
+    w = wl.custom([131072, 3, 700], 8, 1, seed=991)
+    q, k, v = wl.make_host_tensors(w)
+    check(w, q, k, v, run_attn(w, q, k, v), "L=131072")
