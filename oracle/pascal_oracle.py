@@ -22,8 +22,8 @@ What follows the paper directly (Section IV), in its notation:
 * t_i — Section IV-B: an instance violates its answering SLO when its token
   pacer holds too few tokens, i.e. generation is behind the user's pace.
 
-Where the paper is silent this file takes the readings listed in the design
-notes; each is marked "reading" below.  Pins (tests/test_pascal_oracle.py):
+Where the paper is silent this file takes a reading of its own; each is marked
+"reading" where it is applied.  Pins (tests/test_pascal_oracle.py):
 worked tables for both algorithms, the adaptive-migration example of the figure in Section IV-B,
 closed forms for QoE, and invariants of the queue dynamics on seeded traces
 (capacity never exceeded, block ids unique, priority respected, every token
