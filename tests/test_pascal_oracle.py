@@ -89,6 +89,41 @@ def test_adaptive_migration_example():
     assert po.adaptive_migration(1, 1, 0, 0, 5, 1) == 1
 
 
+def _golden(name):
+    import os
+    path = os.path.join(os.path.dirname(os.path.abspath(__file__)), "golden", name)
+    return [ln.split("#")[0].split() for ln in open(path) if ln.split("#")[0].strip()]
+
+
+def test_adaptive_migration_golden_example():
+    rows = _golden("adaptive_migration_example.txt")
+    inst, (cur, want_alg2, want_final) = rows[:-1], map(int, rows[-1])
+    r = [int(x[1]) for x in inst]
+    free = [int(x[2]) for x in inst]
+    t = [bool(int(x[3])) for x in inst]
+    sel = po.select_answering_instance(t, r, [0] * len(r), current=cur)
+    assert sel == want_alg2
+    # the request occupies at least one slot; any headroom from one slot up gives the same answer
+    for headroom in (1, 2):
+        assert po.adaptive_migration(cur, sel, free[cur], free[sel], 1, headroom) == want_final
+
+
+def test_defaults_are_the_papers_constants():
+    import inspect
+    from paper_2602_11530_amd import sched_binding as sb
+    c = {k: float(v) for k, v in _golden("paper_constants.txt")}
+    cfg = po.Config()
+    assert (cfg.quantum, cfg.demote_tokens, cfg.num_instances, cfg.tpot) == \
+        (c["quantum_tokens"], c["demote_tokens"], c["num_instances"], c["target_tpot_s"])
+    d = {k: v.default for k, v in inspect.signature(sb.Scheduler.__init__).parameters.items()}
+    assert (d["quantum"], d["demote_tokens"], d["num_instances"], d["tpot"]) == \
+        (c["quantum_tokens"], c["demote_tokens"], c["num_instances"], c["target_tpot_s"])
+    t = inspect.signature(wl.serving_trace).parameters
+    assert (t["n_requests"].default, t["prompt"].default, t["lo"].default, t["hi"].default) == \
+        (c["trace_requests"], c["prompt_tokens"], c["phase_tokens_min"], c["phase_tokens_max"])
+    assert c["qoe_slo"] == 0.95
+
+
 # ---- QoE and the pacer -----------------------------------------------------------------
 
 def test_qoe_closed_forms():
