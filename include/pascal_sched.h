@@ -153,6 +153,15 @@ int pascal_instance_signals(const pascal_sched* s, int32_t instance, double now,
 
 int pascal_request(const pascal_sched* s, int32_t request, pascal_request_info* out);
 
+/* Token pacer (Section II-C): how many answering tokens the user has been shown by
+ * `now`.  Tokens produced in a burst are held back and released one per
+ * target_tpot_s, so a request that was ahead of its reader keeps streaming
+ * while it is preempted: visible = number of k with d_k <= now, where
+ * d_0 = g_0 and d_k = max(g_k, d_{k-1} + target_tpot_s) over the production
+ * times g. */
+int pascal_request_visible_tokens(const pascal_sched* s, int32_t request, double now,
+                                  int32_t* visible);
+
 /* The request's GPU blocks in table order; returns their number or a negative status. */
 int pascal_request_blocks(const pascal_sched* s, int32_t request, int32_t* blocks,
                           int32_t capacity);

@@ -110,6 +110,11 @@ def qoe(g: Sequence[float], tpot: float) -> float:
     return digested / expected if expected > 0 else 1.0
 
 
+def visible_tokens(g: Sequence[float], tpot: float, now: float) -> int:
+    """Tokens the pacer has released by `now`: those whose reading time has come."""
+    return sum(1 for dk in digest_times(g, tpot) if dk <= now)
+
+
 def pacer_lagging(n_answer_tokens: int, t_first: float, now: float, tpot: float) -> bool:
     """The pacer has run dry: by `now` the user expects more tokens than exist."""
     if n_answer_tokens < 1:

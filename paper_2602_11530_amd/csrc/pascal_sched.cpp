@@ -461,6 +461,22 @@ int pascal_request(const pascal_sched* s, int32_t request, pascal_request_info* 
   return PASCAL_OK;
 }
 
+int pascal_request_visible_tokens(const pascal_sched* s, int32_t request, double now,
+                                  int32_t* visible) {
+  if (!s || !visible) return PASCAL_ERR_NULL;
+  if (request < 0 || request >= (int32_t)s->req.size()) return PASCAL_ERR_ARG;
+  const std::vector<double>& g = s->req[request].answer_times;
+  int32_t n = 0;
+  double d = 0.0;
+  for (size_t k = 0; k < g.size(); ++k) {
+    d = k == 0 ? g[0] : std::max(g[k], d + s->cfg.target_tpot_s);
+    if (d > now) break;   // the release times only grow
+    ++n;
+  }
+  *visible = n;
+  return PASCAL_OK;
+}
+
 int pascal_request_blocks(const pascal_sched* s, int32_t request, int32_t* blocks, int32_t capacity) {
   if (!s) return PASCAL_ERR_NULL;
   if (request < 0 || request >= (int32_t)s->req.size()) return PASCAL_ERR_ARG;

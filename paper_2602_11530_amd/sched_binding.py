@@ -20,7 +20,7 @@ QUEUED, RESIDENT, OFFLOADED, FINISHED = 0, 1, 2, 3
 EXPORTS = (
     "pascal_create", "pascal_destroy", "pascal_submit", "pascal_plan", "pascal_plan_batch",
     "pascal_plan_block_tables", "pascal_ops", "pascal_commit", "pascal_instance_signals",
-    "pascal_request", "pascal_request_blocks", "pascal_status_string",
+    "pascal_request", "pascal_request_blocks", "pascal_request_visible_tokens", "pascal_status_string",
 )
 
 
@@ -79,6 +79,7 @@ def lib() -> ctypes.CDLL:
                                               pi32, pi32, pi32]
         L.pascal_request.argtypes = [vp, i32, ctypes.POINTER(RequestInfo)]
         L.pascal_request_blocks.argtypes = [vp, i32, vp, i32]
+        L.pascal_request_visible_tokens.argtypes = [vp, i32, dbl, pi32]
         L.pascal_status_string.argtypes = [ctypes.c_int]
         L.pascal_status_string.restype = ctypes.c_char_p
         for name in EXPORTS:
@@ -167,6 +168,12 @@ class Scheduler:
         info = RequestInfo()
         _check(lib().pascal_request(self._h, rid, ctypes.byref(info)))
         return info
+
+    def visible_tokens(self, rid: int, now: float) -> int:
+        """Answering tokens the pacer has released to the user by ``now``."""
+        n = ctypes.c_int32()
+        _check(lib().pascal_request_visible_tokens(self._h, rid, now, ctypes.byref(n)))
+        return n.value
 
     def request_blocks(self, rid: int) -> List[int]:
         info = self.request(rid)

@@ -158,6 +158,20 @@ def test_qoe_closed_forms():
     assert po.qoe([], tp) == 1.0 and po.qoe([5.0], tp) == 1.0
 
 
+def test_pacer_release_schedule():
+    # a burst of 10 tokens within 0.1 s, pace 1 s: one token becomes visible per second
+    g = [5.0 + 0.01 * k for k in range(10)]
+    assert [po.visible_tokens(g, 1.0, 5.0 + x) for x in (-0.1, 0.0, 0.99, 1.0, 3.5, 9.0, 100.0)] == \
+        [0, 1, 1, 2, 4, 10, 10]
+    # slower than the pace: every token is visible the moment it exists
+    g = [0.0, 2.0, 4.0]
+    assert [po.visible_tokens(g, 1.0, t) for t in (0.0, 1.9, 2.0, 4.0)] == [1, 1, 2, 3]
+    # a pause after a burst: the buffer bridges it (4 tokens at once, then nothing for 3.5 s)
+    g = [0.0, 0.0, 0.0, 0.0, 3.5]
+    assert [po.visible_tokens(g, 1.0, t) for t in (0.0, 1.0, 2.0, 3.0, 3.4, 3.5, 4.0)] == [1, 2, 3, 4, 4, 4, 5]
+    assert po.visible_tokens([], 1.0, 9.0) == 0
+
+
 def test_pacer_lagging():
     # first token at 10.0, pace 0.1: by 10.35 the reader expects tokens 0..3
     assert not po.pacer_lagging(4, 10.0, 10.35, 0.1)

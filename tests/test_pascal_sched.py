@@ -192,3 +192,5 @@ def test_library_equals_oracle_on_random_walks(seed):
                (q.state, q.phase, q.level, q.instance, q.kv_tokens, len(q.blocks), q.preemptions, q.migrations)
         assert both.lib.request_blocks(rid) == q.blocks
         assert info.qoe == pytest.approx(both.ref.qoe(rid), rel=1e-12)
+        for t in (q.arrival, now / 2, now, now + 50.0):
+            assert both.lib.visible_tokens(rid, t) == po.visible_tokens(q.answer_times, kw["tpot"], t)
