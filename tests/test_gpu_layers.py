@@ -123,3 +123,28 @@ def test_graph_replay_of_decode_steps(device):
             k_h[l], v_h[l] = oracle.kv_append(kn, vn, k_h[l], v_h[l], w.block_tables, w.context_lens)
             assert np.array_equal(to_bits(k_g[l]).reshape(k_h[l].shape), k_h[l])
             check(to_bits(replayed[l]), q, k_h[l], v_h[l], w, f"graph replay step {step} layer {l}")
+
+
+def test_two_instances_decode_concurrently(device):
+    """Two instances on the one GPU, each with its own pools, tables, workspace and stream:
+    their attention calls may overlap in time and must not disturb each other."""
+    rng = np.random.default_rng(71)
+    ws_ = [wl.custom(rng.integers(200, 3000, size=12), 40, 8, seed=71 + i) for i in range(2)]
+    host = [wl.make_host_tensors(w) for w in ws_]
+    dev = [tuple(to_dev(x) for x in h) for h in host]
+    tabs = [(to_dev(w.block_tables), to_dev(w.context_lens)) for w in ws_]
+    alone = [run_attn_dev(w, *d, *t) for w, d, t in zip(ws_, dev, tabs)]
+    torch.cuda.synchronize()
+    streams = [torch.cuda.Stream(device), torch.cuda.Stream(device)]
+    shapes = [shape_of(w) for w in ws_]
+    wss = [torch.empty(pkv.pkv_attn_workspace_bytes(s), dtype=torch.uint8, device=device) for s in shapes]
+    outs = [torch.full(w.q_shape(), 0x7FC1, dtype=torch.int16, device=device) for w in ws_]
+    for rep in range(6):
+        for i in (0, 1):
+            q, k, v = dev[i]
+            pkv.paged_decode_attn(q, k, v, tabs[i][0], tabs[i][1], float(ws_[i].scale), outs[i],
+                                  shapes[i], wss[i], streams[i])
+    torch.cuda.synchronize()
+    for i in (0, 1):
+        assert torch.equal(outs[i], alone[i]), f"instance {i} changed when run next to the other"
+        check(to_bits(outs[i]), *host[i], ws_[i], f"concurrent instance {i}")
