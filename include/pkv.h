@@ -80,7 +80,7 @@ int pkv_attn_workspace_bytes(const pkv_attn_shape* shape /* host */, size_t* out
  * Table entries at index >= ceil(context_lens[s]/B) and slots past the last
  * valid token are never read, whatever they hold.  Dereferenced block ids must
  * lie in [0, num_pool_blocks); the device never follows an id outside that
- * range (the 16 tokens of such a block are left out of the softmax, so a
+ * range (the tokens of such a block are left out of the softmax, so a
  * corrupt table gives a wrong row, not a memory fault), and a negative
  * context_lens[s] counts as 0.  Several requests may map the same block.
  *
