@@ -20,7 +20,9 @@
  * (Section IV-B).  Time is whatever the caller passes as `now` (seconds).
  *
  * Every function returns PASCAL_OK or a negative status; on error nothing
- * changed.  A scheduler object must not be used from two threads at once.
+ * changed (the one exception: PASCAL_ERR_CAPACITY from pascal_plan or
+ * pascal_commit means host memory ran out midway and the object can only be
+ * destroyed).  A scheduler object must not be used from two threads at once.
  */
 #ifndef PASCAL_SCHED_H_
 #define PASCAL_SCHED_H_

@@ -318,11 +318,16 @@ int pascal_create(const pascal_config* c, pascal_sched** out) {
     return PASCAL_ERR_ARG;
   pascal_sched* s = new (std::nothrow) pascal_sched();
   if (!s) return PASCAL_ERR_CAPACITY;
-  s->cfg = *c;
-  s->inst.resize(c->num_instances);
-  for (Instance& ins : s->inst) {
-    ins.free_blocks.resize(c->gpu_blocks);
-    for (int b = 0; b < c->gpu_blocks; ++b) ins.free_blocks[b] = c->gpu_blocks - 1 - b;  // lowest id first
+  try {
+    s->cfg = *c;
+    s->inst.resize(c->num_instances);
+    for (Instance& ins : s->inst) {
+      ins.free_blocks.resize(c->gpu_blocks);
+      for (int b = 0; b < c->gpu_blocks; ++b) ins.free_blocks[b] = c->gpu_blocks - 1 - b;  // lowest id first
+    }
+  } catch (const std::bad_alloc&) {   // no C++ exception may cross the C boundary
+    delete s;
+    return PASCAL_ERR_CAPACITY;
   }
   *out = s;
   return PASCAL_OK;
@@ -335,16 +340,21 @@ int pascal_submit(pascal_sched* s, int32_t prompt_tokens, double now, int32_t* r
   if (!s || !request || !instance) return PASCAL_ERR_NULL;
   if (prompt_tokens < 1) return PASCAL_ERR_ARG;
   if (s->blocks_for(prompt_tokens) > s->cfg.gpu_blocks) return PASCAL_ERR_CAPACITY;
-  const int i = s->select_for_reasoning(now);
-  Request q;
-  q.instance = i;
-  q.prompt = prompt_tokens;
-  q.arrival = now;
-  s->req.push_back(q);
-  const int rid = (int)s->req.size() - 1;
-  s->inst[i].queue[0].push_back(rid);
-  *request = rid;
-  *instance = i;
+  try {
+    const int i = s->select_for_reasoning(now);
+    Request q;
+    q.instance = i;
+    q.prompt = prompt_tokens;
+    q.arrival = now;
+    s->inst[i].queue[0].reserve(s->inst[i].queue[0].size() + 1);
+    s->req.push_back(q);
+    const int rid = (int)s->req.size() - 1;
+    s->inst[i].queue[0].push_back(rid);
+    *request = rid;
+    *instance = i;
+  } catch (const std::bad_alloc&) {
+    return PASCAL_ERR_CAPACITY;
+  }
   return PASCAL_OK;
 }
 
@@ -355,7 +365,11 @@ int pascal_plan(pascal_sched* s, int32_t instance, int32_t* n_selected, int32_t*
   if (!s || !n_selected || !n_ops || !n_op_blocks) return PASCAL_ERR_NULL;
   if (bad_instance(s, instance)) return PASCAL_ERR_ARG;
   if (s->inst[instance].awaiting_commit) return PASCAL_ERR_STATE;
-  s->plan(instance);
+  try {
+    s->plan(instance);
+  } catch (const std::bad_alloc&) {   // host memory exhausted: the scheduler state is no longer usable
+    return PASCAL_ERR_CAPACITY;
+  }
   const Instance& ins = s->inst[instance];
   *n_selected = (int32_t)ins.selected.size();
   *n_ops = (int32_t)ins.ops.size();
@@ -419,7 +433,11 @@ int pascal_commit(pascal_sched* s, int32_t instance, double now, const int32_t* 
   if (n > 0 && !token_kinds) return PASCAL_ERR_NULL;
   for (int32_t k = 0; k < n; ++k)
     if (token_kinds[k] < PASCAL_TOKEN || token_kinds[k] > PASCAL_END_OF_SEQUENCE) return PASCAL_ERR_ARG;
-  s->commit(instance, now, token_kinds);
+  try {
+    s->commit(instance, now, token_kinds);
+  } catch (const std::bad_alloc&) {
+    return PASCAL_ERR_CAPACITY;
+  }
   *n_ops = (int32_t)ins.ops.size();
   *n_op_blocks = (int32_t)ins.op_blocks.size();
   return PASCAL_OK;
