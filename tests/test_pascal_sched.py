@@ -194,3 +194,17 @@ def test_library_equals_oracle_on_random_walks(seed):
         assert info.qoe == pytest.approx(both.ref.qoe(rid), rel=1e-12)
         for t in (q.arrival, now / 2, now, now + 50.0):
             assert both.lib.visible_tokens(rid, t) == po.visible_tokens(q.answer_times, kw["tpot"], t)
+
+
+def test_host_fuzz_under_sanitizers(tmp_path):
+    """The scheduler's C++ source compiled with AddressSanitizer and UBSan into a small stress
+    program (tests/sched_fuzz.cpp): random arrivals, iterations and token kinds on tiny pools,
+    block conservation checked after every call."""
+    import subprocess
+    exe = str(tmp_path / "sched_fuzz")
+    subprocess.check_call(["g++", "-O1", "-g", "-std=c++17", "-fsanitize=address,undefined",
+                           "-fno-sanitize-recover=all", "-static-libasan", "-I", os.path.join(ROOT, "include"),
+                           os.path.join(ROOT, "tests", "sched_fuzz.cpp"),
+                           os.path.join(ROOT, "paper_2602_11530_amd", "csrc", "pascal_sched.cpp"), "-o", exe])
+    p = subprocess.run([exe, "20"], capture_output=True, text=True, timeout=300)
+    assert p.returncode == 0 and p.stdout.strip() == "clean", p.stderr[-2000:]
