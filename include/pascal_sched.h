@@ -63,6 +63,11 @@ extern "C" {
 #define PASCAL_OFFLOADED 2       /* KV in the instance's host store                      */
 #define PASCAL_FINISHED 3
 
+/* The two ablations of the paper's Section V-D: a request stays where it did its
+ * reasoning; or Algorithm 2's choice is followed without the adaptive override. */
+#define PASCAL_FLAG_NO_MIGRATION 1
+#define PASCAL_FLAG_NOT_ADAPTIVE 2
+
 typedef struct {
   int32_t num_instances;   /* >= 1 (the paper evaluates 8, Section V-A)                  */
   int32_t gpu_blocks;      /* KV blocks of one instance's pool                           */
@@ -72,7 +77,7 @@ typedef struct {
   int32_t headroom_blocks; /* free blocks that count as "sufficient memory" in the
                               adaptive-migration rule                                    */
   int32_t max_batch;       /* most requests in one iteration's batch; 0 = no limit       */
-  int32_t reserved;        /* 0                                                          */
+  int32_t flags;           /* 0, or PASCAL_FLAG_* ored together                          */
   double target_tpot_s;    /* the reader's pace, seconds per answering token (0.1)       */
 } pascal_config;
 

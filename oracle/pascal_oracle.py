@@ -142,6 +142,8 @@ class Config:
     headroom_blocks: int = 1
     tpot: float = 0.1               # target seconds per answering token (100 ms, Section III)
     max_batch: int = 0              # 0 = no cap
+    migration: bool = True          # False: the "no migration" ablation of Section V-D
+    adaptive: bool = True           # False: Algorithm 2's choice without the adaptive override
 
 
 @dataclass
@@ -331,11 +333,15 @@ class Cluster:
     def _phase_transition(self, q: Request, now: float) -> List[Op]:
         """Algorithm 2, then the adaptive override; the request has already left its queue."""
         n, cur = self.cfg.num_instances, q.instance
-        sel = select_answering_instance([self.t(j, now) for j in range(n)],
-                                        [self.r(j) for j in range(n)],
-                                        [self.a(j) for j in range(n)], current=cur)
-        dst = adaptive_migration(cur, sel, self.free_blocks(cur), self.free_blocks(sel),
-                                 len(q.blocks), self.cfg.headroom_blocks)
+        sel = cur
+        if self.cfg.migration:
+            sel = select_answering_instance([self.t(j, now) for j in range(n)],
+                                            [self.r(j) for j in range(n)],
+                                            [self.a(j) for j in range(n)], current=cur)
+        dst = sel
+        if self.cfg.adaptive:
+            dst = adaptive_migration(cur, sel, self.free_blocks(cur), self.free_blocks(sel),
+                                     len(q.blocks), self.cfg.headroom_blocks)
         q.phase, q.level, q.quantum_used, q.quanta_done = ANSWERING, LOW, 0, 0
         ops: List[Op] = []
         if dst != cur:

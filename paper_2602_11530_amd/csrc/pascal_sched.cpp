@@ -207,9 +207,9 @@ struct pascal_sched {
   void phase_transition(Instance& log, int rid, double now) {
     Request& q = req[rid];
     const int cur = q.instance;
-    const int sel = select_for_answering(now, cur);
+    const int sel = (cfg.flags & PASCAL_FLAG_NO_MIGRATION) ? cur : select_for_answering(now, cur);
     int dst = sel;
-    if (sel != cur) {
+    if (sel != cur && !(cfg.flags & PASCAL_FLAG_NOT_ADAPTIVE)) {
       // adaptive migration: stay when there is room here and none there
       const bool room_here = (int)inst[cur].free_blocks.size() >= cfg.headroom_blocks;
       const bool room_there =
@@ -314,7 +314,7 @@ int pascal_create(const pascal_config* c, pascal_sched** out) {
   if (!c || !out) return PASCAL_ERR_NULL;
   if (c->num_instances < 1 || c->num_instances > 4096 || c->gpu_blocks < 1 || c->block_tokens < 1 ||
       c->quantum_tokens < 1 || c->demote_tokens < 1 || c->headroom_blocks < 0 || c->max_batch < 0 ||
-      !(c->target_tpot_s > 0.0))
+      !(c->target_tpot_s > 0.0) || (c->flags & ~(PASCAL_FLAG_NO_MIGRATION | PASCAL_FLAG_NOT_ADAPTIVE)))
     return PASCAL_ERR_ARG;
   pascal_sched* s = new (std::nothrow) pascal_sched();
   if (!s) return PASCAL_ERR_CAPACITY;

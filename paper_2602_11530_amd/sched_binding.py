@@ -15,6 +15,7 @@ LIB_PATH = os.path.join(os.path.dirname(os.path.abspath(__file__)), "libpascal_s
 TOKEN, END_OF_REASONING, END_OF_SEQUENCE = 0, 1, 2
 OP_OFFLOAD, OP_RELOAD, OP_PREFILL, OP_GROW, OP_MIGRATE, OP_MIGRATE_HOST, OP_FREE = 1, 2, 3, 4, 5, 6, 7
 REASONING, ANSWERING = 0, 1
+FLAG_NO_MIGRATION, FLAG_NOT_ADAPTIVE = 1, 2
 QUEUED, RESIDENT, OFFLOADED, FINISHED = 0, 1, 2, 3
 
 EXPORTS = (
@@ -29,7 +30,7 @@ class Config(ctypes.Structure):
     _fields_ = [("num_instances", ctypes.c_int32), ("gpu_blocks", ctypes.c_int32),
                 ("block_tokens", ctypes.c_int32), ("quantum_tokens", ctypes.c_int32),
                 ("demote_tokens", ctypes.c_int32), ("headroom_blocks", ctypes.c_int32),
-                ("max_batch", ctypes.c_int32), ("reserved", ctypes.c_int32),
+                ("max_batch", ctypes.c_int32), ("flags", ctypes.c_int32),
                 ("target_tpot_s", ctypes.c_double)]
 
 
@@ -101,9 +102,11 @@ OpTuple = Tuple[int, int, int, Tuple[int, ...], int, Tuple[int, ...]]
 
 class Scheduler:
     def __init__(self, num_instances=8, gpu_blocks=1024, block_tokens=16, quantum=500,
-                 demote_tokens=5000, headroom_blocks=1, tpot=0.1, max_batch=0):
+                 demote_tokens=5000, headroom_blocks=1, tpot=0.1, max_batch=0, migration=True,
+                 adaptive=True):
+        flags = (0 if migration else FLAG_NO_MIGRATION) | (0 if adaptive else FLAG_NOT_ADAPTIVE)
         self.cfg = Config(num_instances, gpu_blocks, block_tokens, quantum, demote_tokens,
-                          headroom_blocks, max_batch, 0, tpot)
+                          headroom_blocks, max_batch, flags, tpot)
         self._h = ctypes.c_void_p()
         _check(lib().pascal_create(ctypes.byref(self.cfg), ctypes.byref(self._h)))
 

@@ -89,7 +89,9 @@ class Both:
                                         quantum=kw.get("quantum", 500),
                                         demote_tokens=kw.get("demote_tokens", 5000),
                                         headroom_blocks=kw.get("headroom_blocks", 1),
-                                        tpot=kw.get("tpot", 0.1), max_batch=kw.get("max_batch", 0)))
+                                        tpot=kw.get("tpot", 0.1), max_batch=kw.get("max_batch", 0),
+                                        migration=kw.get("migration", True),
+                                        adaptive=kw.get("adaptive", True)))
         self.n = kw["num_instances"]
         self.calls = 0
 
@@ -126,6 +128,8 @@ class Both:
     (dict(num_instances=3, gpu_blocks=600, demote_tokens=3000), 40, 6.0),     # memory pressure, demotion
     (dict(num_instances=2, gpu_blocks=300, quantum=100, headroom_blocks=8), 30, 2.0),
     (dict(num_instances=4, gpu_blocks=400, max_batch=3, tpot=0.02), 40, 8.0), # capped batch, strict pace
+    (dict(num_instances=3, gpu_blocks=600, migration=False), 40, 6.0),        # ablation: no migration
+    (dict(num_instances=3, gpu_blocks=600, adaptive=False), 40, 6.0),         # ablation: no adaptive override
 ])
 def test_library_equals_oracle_on_traces(kw, n_requests, rate):
     trace = wl.serving_trace(n_requests=n_requests, rate_per_s=rate, seed=wl.BASE_SEED + 61)
@@ -138,6 +142,8 @@ def test_library_equals_oracle_on_traces(kw, n_requests, rate):
                 kinds[op[0]] = kinds.get(op[0], 0) + 1
     print(f"{kw}: {len(log)} calls, orders by kind {dict(sorted(kinds.items()))}")
     assert kinds.get(sb.OP_PREFILL) == n_requests and kinds.get(sb.OP_FREE) == n_requests
+    if not kw.get("migration", True):
+        assert sb.OP_MIGRATE not in kinds and sb.OP_MIGRATE_HOST not in kinds
     for rid in range(n_requests):
         info, q = both.lib.request(rid), both.ref.req[rid]
         assert info.state == sb.FINISHED == q.state
@@ -159,7 +165,8 @@ def test_library_equals_oracle_on_random_walks(seed):
     kw = dict(num_instances=n_inst, gpu_blocks=int(rng.integers(6, 40)), block_tokens=int(rng.choice([1, 4, 16])),
               quantum=int(rng.integers(1, 12)), demote_tokens=int(rng.integers(8, 200)),
               headroom_blocks=int(rng.integers(0, 4)), tpot=float(rng.choice([0.01, 0.05, 0.3])),
-              max_batch=int(rng.choice([0, 0, 1, 3])))
+              max_batch=int(rng.choice([0, 0, 1, 3])), migration=bool(rng.random() < 0.8),
+              adaptive=bool(rng.random() < 0.8))
     both = Both(**kw)
     cap_tokens = kw["gpu_blocks"] * kw["block_tokens"]
     now, live = 0.0, 0
