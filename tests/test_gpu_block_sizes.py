@@ -8,19 +8,24 @@ import oracle
 from paper_2602_11530_amd import binding as pkv
 from paper_2602_11530_amd import workloads as wl
 
-from gpu_util import MAX_ABS, REL_L2, assert_launchable, run_attn, run_attn_dev, shape_of, to_bits, to_dev
+from gpu_util import (MAX_ABS, REL_L2, abs_error_within_bar, assert_launchable, run_attn, run_attn_dev,
+                      shape_of, to_bits, to_dev)
 
 pytestmark = pytest.mark.gpu
 
 EDGE = [1, 15, 16, 17, 31, 32, 33, 47, 48, 49, 63, 64, 65, 0, 127, 128, 129, 511, 512, 513, 1000, 2]
 
 
-def check(w, q, k, v, got, what):
+def check(w, q, k, v, got, what, large_outputs_possible=False):
     ref = oracle.paged_decode_attn(q, k, v, w.block_tables, w.context_lens, w.scale)
     c = oracle.compare(got, ref)
     print(f"{what}: {c}", flush=True)
     assert np.isfinite(wl.bf16_bits_to_f64(got)).all()
-    assert c["max_abs"] <= MAX_ABS and c["rel_l2"] <= REL_L2 and c["worst_seq_rel_l2"] <= 2 * REL_L2, c
+    assert c["rel_l2"] <= REL_L2 and c["worst_seq_rel_l2"] <= 2 * REL_L2, c
+    if large_outputs_possible:      # batches full of one- to three-token requests
+        assert abs_error_within_bar(got, ref), c
+    else:
+        assert c["max_abs"] <= MAX_ABS, c
 
 
 @pytest.mark.parametrize("B", [32, 64])
@@ -107,3 +112,24 @@ def test_cfg2_shape_with_blocks_of_64(device):
         times[B] = e0.elapsed_time(e1) / 50
         check(w, to_bits(q), to_bits(k), to_bits(v), to_bits(out), f"cfg2 lengths, B={B}")
         print(f"B={B}: {times[B]:.4f} ms, {w.attn_algorithmic_bytes() / times[B] / 1e6:.0f} GB/s", flush=True)
+
+
+@pytest.mark.parametrize("case", range(48))
+def test_random_shapes_all_block_sizes(device, case):
+    """The seeded corner-case batches of the stream decomposition, with the block size drawn too
+    (the partition size is raised to a multiple of it)."""
+    from test_gpu_attn import _random_case
+    rng = np.random.default_rng(12000 + case)
+    lens, hq, hkv, P = _random_case(rng, case)
+    B = int(rng.choice([16, 32, 64]))
+    if P and P % B:
+        P = B * (P // B + 1)
+    need = int(((lens + B - 1) // B).sum())
+    w = wl.custom(lens, hq, hkv, seed=1500 + case, partition_size=P, block_size=B,
+                  num_pool_blocks=need + int(rng.integers(1, 50)))
+    q, k, v = wl.make_host_tensors(w, poison_unused=True)
+    got = run_attn(w, q, k, v)
+    check(w, q, k, v, got, f"case {case}: B={B} S={len(lens)} hq={hq} hkv={hkv} P={P} tokens={int(lens.sum())}",
+          large_outputs_possible=True)
+    for s in np.nonzero(lens == 0)[0]:
+        assert not got.reshape(w.q_shape())[s].any()
