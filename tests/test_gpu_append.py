@@ -69,3 +69,19 @@ def test_decode_loop_append_then_attend(device):
         c = oracle.compare(to_bits(out), ref)
         print(f"decode step {step}: {c}", flush=True)
         assert c["max_abs"] <= MAX_ABS and c["rel_l2"] <= REL_L2, c
+
+
+def test_append_honours_the_length_bound(device):
+    """With max_context_len below a request's length the new row lands at the bound's last
+    position, where attention with the same bound will look for it."""
+    w = wl.custom([300, 90], 8, 2, seed=19, maxb=32)
+    rng = np.random.default_rng(19)
+    _, k, v = wl.make_host_tensors(w)
+    k_new, v_new = wl.normal_bf16(rng, (2, 2, 128)), wl.normal_bf16(rng, (2, 2, 128))
+    k_d, v_d = to_dev(k), to_dev(v)
+    pkv.kv_append(to_dev(k_new), to_dev(v_new), k_d, v_d, to_dev(w.block_tables),
+                  to_dev(w.context_lens), shape_of(w, max_context_len=128))
+    torch.cuda.synchronize()
+    wk, wv = oracle.kv_append(k_new, v_new, k, v, w.block_tables, np.array([128, 90], np.int32))
+    assert np.array_equal(to_bits(k_d).reshape(k.shape), wk)
+    assert np.array_equal(to_bits(v_d).reshape(v.shape), wv)

@@ -285,3 +285,20 @@ def test_one_very_long_request(device):
     w = wl.custom([131072, 3, 700], 8, 1, seed=991)
     q, k, v = wl.make_host_tensors(w)
     check(w, q, k, v, run_attn(w, q, k, v), "L=131072")
+
+
+def test_length_bound_clamps_and_negative_length_is_empty(device):
+    """A request longer than max_context_len is attended up to the bound; a negative length
+    counts as zero.  Both are what the header promises for inputs a scheduler should not send."""
+    w = wl.custom([300, 90, 17, 40], 8, 2, seed=18, maxb=32)
+    q, k, v = wl.make_host_tensors(w)
+    lens = w.context_lens.copy()
+    lens[3] = -5
+    q_d, k_d, v_d = (to_dev(x) for x in (q, k, v))
+    got = to_bits(run_attn_dev(w, q_d, k_d, v_d, to_dev(w.block_tables), to_dev(lens),
+                               max_context_len=128, check_tables=False))
+    torch.cuda.synchronize()
+    clamped = wl.custom([128, 90, 17, 0], 8, 2, seed=18, maxb=32)
+    clamped.block_tables = w.block_tables
+    check(clamped, q, k, v, got, "clamped to 128, negative length")
+    assert not got.reshape(w.q_shape())[3].any()
