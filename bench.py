@@ -35,7 +35,10 @@ def parse():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=200)
     ap.add_argument("--warmup", type=int, default=20)
-    ap.add_argument("--workload", default="cfg2", choices=["cfg1", "cfg2", "cfg3"])
+    ap.add_argument("--workload", default="cfg2", choices=["cfg1", "cfg2", "cfg3", "cfg4"],
+                    help="cfg4: the full-depth phase-mixed batch, every layer's pools resident, one "
+                         "multi-layer attention call per step (no migration; use --steps 5)")
+    ap.add_argument("--layers", type=int, default=0, help="cfg4 only: layers to keep resident (0 = 64, or what fits)")
     ap.add_argument("--partition", type=int, default=None,
                     help="split-K partition in tokens (default: the workload's; 0 = library picks)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
@@ -61,6 +64,87 @@ def device_tensors(w, device):
     return q, pools[0], pools[1]
 
 
+def full_depth(args, dev):
+    """Config 4: 96 requests (70 % reasoning, 30 % answering lengths), one K and one V pool per
+    layer, all resident; a step is one decode iteration's attention in every layer."""
+    import numpy as np
+    import torch
+
+    from paper_2602_11530_amd import binding as pkv
+    from paper_2602_11530_amd import workloads as wl
+
+    w = wl.cfg4_phase_mixed()
+    free, _ = torch.cuda.mem_get_info(dev)
+    per_layer = 2 * w.num_pool_blocks * w.block_bytes + (4 << 20)
+    n_layers = max(1, min(args.layers or w.num_layers, int((free - (24 << 30)) // per_layer)))
+    g = torch.Generator(device=dev)
+    layers = []
+    for l in range(n_layers):
+        g.manual_seed(w.seed + 1000 * l + 17)
+        q = torch.randn(w.q_shape(), generator=g, device=dev, dtype=torch.float32).to(torch.bfloat16)
+        pools = []
+        for _ in range(2):
+            p = torch.empty(w.pool_shape(), dtype=torch.bfloat16, device=dev)
+            flat = p.view(-1)
+            for o in range(0, flat.numel(), 1 << 28):
+                n = min(1 << 28, flat.numel() - o)
+                flat[o:o + n] = torch.randn(n, generator=g, device=dev, dtype=torch.float32)
+            pools.append(p)
+        layers.append((q, pools[0], pools[1]))
+    outs = [torch.empty(w.q_shape(), dtype=torch.bfloat16, device=dev) for _ in range(n_layers)]
+    tables = torch.from_numpy(w.block_tables).to(dev)
+    lens = torch.from_numpy(w.context_lens).to(dev)
+    shape = pkv.make_shape(w.num_seqs, w.num_q_heads, w.num_kv_heads, w.max_blocks_per_seq,
+                           w.num_pool_blocks, max_context_len=int(w.context_lens.max()))
+    ws = torch.empty(pkv.pkv_attn_workspace_bytes(shape), dtype=torch.uint8, device=dev)
+    ptrs = [pkv.pointer_array(x) for x in ([l[0] for l in layers], [l[1] for l in layers],
+                                           [l[2] for l in layers], outs)]
+    stream = torch.cuda.current_stream()
+
+    def step():
+        pkv.paged_decode_attn_layers(ptrs[0], ptrs[1], ptrs[2], tables, lens, float(w.scale), ptrs[3],
+                                     shape, ws, stream)
+
+    for _ in range(max(1, min(args.warmup, 3))):
+        step()
+    torch.cuda.synchronize()
+    ev = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True))
+          for _ in range(args.steps)]
+    t0 = time.perf_counter()
+    for a, b in ev:
+        a.record(stream)
+        step()
+        b.record(stream)
+    torch.cuda.synchronize()
+    wall = time.perf_counter() - t0
+    ms = np.array([a.elapsed_time(b) for a, b in ev])
+    step_bytes = w.attn_algorithmic_bytes() * n_layers
+    value = step_bytes / (wall / args.steps) / 1e9
+    gbps = step_bytes / (ms.mean() * 1e-3) / 1e9
+    res = {
+        "metric": "paged decode attn HBM GB/s (% of peak) + KV tokens attended/s, Qwen-32B shape",
+        "value": round(value, 1), "unit": "GB/s", "n_gpus": 1, "steps": args.steps,
+        "warmup": max(1, min(args.warmup, 3)), "ms_per_step": round(wall * 1e3 / args.steps, 3),
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "bf16",
+        "data": "synthetic",
+        "config": {"workload": w.name, "num_seqs": w.num_seqs, "q_heads": w.num_q_heads,
+                   "kv_heads": w.num_kv_heads, "layers_resident": n_layers,
+                   "resident_kv_bytes": n_layers * 2 * w.num_pool_blocks * w.block_bytes,
+                   "total_context_tokens": w.total_tokens,
+                   "step": "paged_decode_attn_layers over every resident layer"},
+        "step_algorithmic_bytes": step_bytes,
+        "pct_of_hbm_peak": round(100 * value / HBM_PEAK_GBPS, 2),
+        "attn": {"ms_mean": round(float(ms.mean()), 3), "GBps": round(gbps, 1),
+                 "kv_tokens_attended_per_s": round(w.total_tokens * n_layers / (ms.mean() * 1e-3), 1),
+                 "token_definition": "one cached position of one request attended in one layer by all its heads"},
+        "roofline": {"bound": "hbm", "kernel": "attn_stream_kernel + merge, all layers of a step",
+                     "achieved": round(gbps, 1), "peak": HBM_PEAK_GBPS, "unit": "GB/s",
+                     "frac": round(gbps / HBM_PEAK_GBPS, 4), "traffic": None},
+        "cpu_baseline": None,
+    }
+    print(json.dumps(res), flush=True)
+
+
 def main():
     args = parse()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
@@ -79,6 +163,8 @@ def main():
     dev = torch.device("cuda:0")
     torch.cuda.set_device(dev)
 
+    if args.workload == "cfg4":
+        return full_depth(args, dev)
     w = {"cfg1": wl.cfg1_tiny, "cfg2": wl.cfg2_qwen32b, "cfg3": wl.cfg3_long_cot}[args.workload]()
     if args.partition is not None:
         w.partition_size = args.partition
