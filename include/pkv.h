@@ -46,9 +46,12 @@ typedef struct {
   int32_t head_dim;           /* D: 128                                                  */
   int32_t block_size;         /* B: tokens per physical block: 16, 32 or 64              */
   int32_t max_blocks_per_seq; /* MAXB: row stride of block_tables, >= ceil(L_s/B)        */
-  int32_t partition_size;     /* P: most tokens of a request that one partial result may
-                                 cover before the split-K merge: a multiple of B in
-                                 [B, 65536], or 0 to let the library choose              */
+  int32_t partition_size;     /* P: split-K partition, the most tokens of a request that
+                                 one partial result (max, sum, row) may cover: a multiple
+                                 of B in [B, 65536], or 0 to let the library choose.
+                                 Partial results of one request and KV head that the same
+                                 wavefront produced are merged on chip; the merge pass
+                                 combines the rest.  P does not change the workspace.    */
   int32_t max_context_len;    /* host upper bound on every context_lens[s]; 0 means
                                  MAXB*B.  A smaller bound only shrinks the launch;
                                  a request longer than the bound is attended up to it.   */

@@ -35,19 +35,17 @@ __global__ __launch_bounds__(kRowsPerGroup * 64) void attn_reduce_kernel(AttnLau
   const int s = row / a.Hq, h = row - s * a.Hq;
   const int kvh = h / a.G, g = h - kvh * a.G;
   const int* cumB = a.ws_cum;
-  const int* cumNP = a.ws_cum + (a.S + 1);
   const int nb = cumB[s + 1] - cumB[s];
   uint32_t* dst = (uint32_t*)(a.out + (int64_t)row * kHeadDim) + lane;
   if (nb <= 0) { *dst = 0u; return; }   // an empty request owes a zero row
 
   const int64_t T = (int64_t)a.Hkv * cumB[a.S];
   const int64_t W = min((int64_t)kStreamWaves, T);
-  const int nps = cumNP[s + 1] - cumNP[s];
   const int64_t pos_a = (int64_t)a.Hkv * cumB[s] + (int64_t)kvh * nb;   // the segment's first block
-  const int gp0 = a.Hkv * cumNP[s] + kvh * nps;
-  const int first = gp0 + share_owner(pos_a, T, W);
-  const int last = gp0 + (nps - 1) + share_owner(pos_a + nb - 1, T, W);
-  const int np = last - first + 1;   // records of this row, a neutral filler possibly among them
+  const int seg = s * a.Hkv + kvh;
+  const int first = seg + share_owner(pos_a, T, W);
+  const int last = seg + share_owner(pos_a + nb - 1, T, W);
+  const int np = last - first + 1;   // one record per wavefront that streamed part of this segment
 
   const int rec_floats = record_floats(a.G);
   auto stats = [&](int p) -> float2 {   // (max, sum) of record p for this head
@@ -69,7 +67,7 @@ __global__ __launch_bounds__(kRowsPerGroup * 64) void attn_reduce_kernel(AttnLau
     float w = 0.f;
     if (p < np) {
       const float2 ml = stats(p);
-      // A record whose blocks were all unmapped, or a filler, carries max = -inf, sum = 0.
+      // A record whose blocks were all unmapped carries max = -inf, sum = 0.
       w = (ml.x == kNegInf) ? 0.f : __builtin_amdgcn_exp2f(ml.x - M);
       lsum = __builtin_fmaf(w, ml.y, lsum);
     }

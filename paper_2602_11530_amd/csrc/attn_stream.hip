@@ -7,9 +7,11 @@
 // stream (layout in pkv_kernels.h) that is cut into kStreamWaves equal shares:
 // every wavefront reads the same number of blocks (+-1), starts streaming at
 // once, never idles between requests, and there is no tail of late workgroups.
-// A wavefront emits one partial record per run (a stretch of its share inside
-// one request, one KV head and one P-token partition); the merge pass combines
-// the records of each (request, query head).
+// A wavefront computes one partial result per run (a stretch of its share inside
+// one request, one KV head and one P-token partition), folds the runs of one
+// (request, KV head) into a single record while that record is still parked in
+// LDS, and writes one record per (wavefront, request, KV head); the merge pass
+// combines the records of each (request, query head).
 //
 // Per 16-token block, lane = 16*c + n:
 //   S^T = K . Q^T   four v_mfma_f32_16x16x32_bf16 (k = 32 dims each).
@@ -101,11 +103,10 @@ constexpr int kMetaSegFirst = 1 << 9;
 __global__ __launch_bounds__(kStreamWavesPerGroup * 64) void attn_stream_kernel(AttnLaunch a) {
   extern __shared__ int smem[];
   int* cumB = smem;                  // [S+1] blocks before request s
-  int* cumNP = smem + (a.S + 1);     // [S+1] partitions before request s
-  int* lens = smem + 2 * (a.S + 1);  // [S]   clamped context lengths
+  int* lens = smem + (a.S + 1);      // [S]   clamped context lengths
   // then room for rec_buffered finished records per wavefront, 16-byte aligned
   const int rec_floats = record_floats(a.G);
-  float* rec_stage = (float*)(smem + ((3 * (a.S + 1) + 3) & ~3)) +
+  float* rec_stage = (float*)(smem + ((2 * (a.S + 1) + 3) & ~3)) +
                      (threadIdx.x >> 6) * a.rec_buffered * rec_floats;
 
   const int wave = threadIdx.x >> 6;
@@ -116,27 +117,25 @@ __global__ __launch_bounds__(kStreamWavesPerGroup * 64) void attn_stream_kernel(
 
   // Prefix sums over the requests (wavefront 0 of every workgroup; S is small).
   if (wave == 0) {
-    int runB = 0, runP = 0;
+    int runB = 0;
     for (int base = 0; base < S; base += 64) {
       const int i = base + lane;
       const int L = (i < S) ? min(max(a.context_lens[i], 0), a.max_ctx) : 0;
       const int nb = (L + kBlockTokens - 1) / kBlockTokens;
-      const int np = (nb + bpp - 1) / bpp;
-      int xb = nb, xp = np;
+      int xb = nb;
 #pragma unroll
       for (int o = 1; o < 64; o <<= 1) {
-        const int yb = __shfl_up(xb, o), yp = __shfl_up(xp, o);
-        if (lane >= o) { xb += yb; xp += yp; }
+        const int yb = __shfl_up(xb, o);
+        if (lane >= o) xb += yb;
       }
-      if (i < S) { lens[i] = L; cumB[i] = runB + xb - nb; cumNP[i] = runP + xp - np; }
+      if (i < S) { lens[i] = L; cumB[i] = runB + xb - nb; }
       runB += __shfl(xb, 63);
-      runP += __shfl(xp, 63);
     }
-    if (lane == 0) { cumB[S] = runB; cumNP[S] = runP; }
+    if (lane == 0) cumB[S] = runB;
   }
   __syncthreads();
-  if (blockIdx.x == 0) {   // the merge pass reads the same prefix arrays
-    for (int i = threadIdx.x; i < 2 * (S + 1); i += blockDim.x) a.ws_cum[i] = smem[i];
+  if (blockIdx.x == 0) {   // the merge pass reads the same prefix array
+    for (int i = threadIdx.x; i < S + 1; i += blockDim.x) a.ws_cum[i] = smem[i];
   }
 
   // Every participating wavefront gets at least one block, so that consecutive
@@ -165,7 +164,6 @@ __global__ __launch_bounds__(kStreamWavesPerGroup * 64) void attn_stream_kernel(
     const int o = pos - Hkv * cumB[s];
     const int kvh = o / nb;
     const int b = o - kvh * nb;
-    const int nps = cumNP[s + 1] - cumNP[s];
     int ntok = min(kBlockTokens, lens[s] - kBlockTokens * b);
     // unit b of the request lies in physical block b / upb, at unit b % upb of the KV head's rows
     const int tb = b / a.upb;
@@ -178,28 +176,13 @@ __global__ __launch_bounds__(kStreamWavesPerGroup * 64) void attn_stream_kernel(
     const bool seg_first = (b == 0) || (j == 0);
     d.meta = ntok | (last ? kMetaLast : 0) | (seg_first ? kMetaSegFirst : 0);
     d.qrow = s * a.Hq + kvh * G;
-    d.slot = Hkv * cumNP[s] + kvh * nps + b / bpp + w;
+    d.slot = s * Hkv + kvh + w;
     return d;
   };
 
   Window dA = describe(0);
   Window dB = dA;   // described after the first KV loads are on their way (below)
   int jbase = 0;
-
-  // When this share begins exactly on a partition boundary the previous
-  // wavefront's last slot and this one's first differ by two; the slot between
-  // them belongs to nobody and is given a neutral record so that the merge may
-  // walk a segment's slots without gaps.
-  {
-    const int slot0 = __builtin_amdgcn_readfirstlane(dA.slot);
-    const int qrow0 = __builtin_amdgcn_readfirstlane(dA.qrow);
-    const int s0 = qrow0 / a.Hq;
-    const int kvh0 = (qrow0 - s0 * a.Hq) / G;
-    const int b0 = (pos0 - Hkv * cumB[s0]) - kvh0 * (cumB[s0 + 1] - cumB[s0]);
-    if (w > 0 && b0 > 0 && b0 % bpp == 0 && lane < G)
-      *(float2*)(a.ws_rec + (int64_t)(slot0 - 1) * rec_floats + G * kHeadDim + 2 * lane) =
-          make_float2(kNegInf, 0.f);
-  }
 
   const int64_t head_elems = (int64_t)kBlockTokens * kHeadDim;  // one (block, KV head) slab
   const int tau = 4 * (n & 3) + (n >> 2);
@@ -240,6 +223,7 @@ __global__ __launch_bounds__(kStreamWavesPerGroup * 64) void attn_stream_kernel(
   // microseconds per burst of stores however few bytes it carries.
   int nrec = 0;        // records parked in LDS
   int rec_slots = 0;   // lane r: slot of parked record r
+  bool seg_open = false;   // the newest parked record belongs to the segment being streamed
   auto drain_records = [&]() {
     for (int r = 0; r < nrec; ++r) {
       const int slot = __builtin_amdgcn_readlane(rec_slots, r);
@@ -257,6 +241,7 @@ __global__ __launch_bounds__(kStreamWavesPerGroup * 64) void attn_stream_kernel(
 
     if (meta & kMetaSegFirst) {
       // A new (request, KV head): fetch its query group.
+      seg_open = false;
       const int qrow = __builtin_amdgcn_readlane(dA.qrow, idx);
       const u32x4* qp = (const u32x4*)(a.q + (int64_t)(qrow + min(n, G - 1)) * kHeadDim) + c;
 #pragma unroll
@@ -332,24 +317,57 @@ __global__ __launch_bounds__(kStreamWavesPerGroup * 64) void attn_stream_kernel(
     }
 
     if (meta & kMetaLast) {
-      // The run ends here: store its partial record and start afresh.
-      const int slot = __builtin_amdgcn_readlane(dA.slot, idx);
+      // The run ends here.  The first run of a (request, KV head) in this share
+      // parks its partial result in LDS as a new record, assembled in its memory
+      // order; every later run of the same segment (the next P-token partitions)
+      // is folded into that parked record with the split-K merge formula, so
+      // memory sees one record per (wavefront, segment) however small P is.
       float lt = l + __shfl_xor(l, 16);
       lt += __shfl_xor(lt, 32);
-      // The record is assembled in LDS in its memory order and parked there.
-      float* rec = rec_stage + nrec * rec_floats;
+      if (!seg_open) {
+        if (nrec == a.rec_buffered) drain_records();
+        const int slot = __builtin_amdgcn_readlane(dA.slot, idx);
+        rec_slots = (lane == nrec) ? slot : rec_slots;
+        ++nrec;
+      }
+      float* rec = rec_stage + (nrec - 1) * rec_floats;
+      float keep[4] = {0.f, 0.f, 0.f, 0.f}, add[4] = {1.f, 1.f, 1.f, 1.f};
+      if (seg_open) {
+        // parked (m1, l1, rows1) and this run's (m, lt, o): weights 2^(m1-M) and 2^(m-M),
+        // a side whose maximum is -inf (nothing valid seen) gets weight 0 by select
+        const f32x2 st = *(const f32x2*)(rec + G * kHeadDim + 2 * n);
+        const float M = fmaxf(st.x, m);
+        const float w1 = (st.x == kNegInf) ? 0.f : __builtin_amdgcn_exp2f(st.x - M);
+        const float w2 = (m == kNegInf) ? 0.f : __builtin_amdgcn_exp2f(m - M);
+        lt = w1 * st.y + w2 * lt;
+        m = M;
+#pragma unroll
+        for (int r = 0; r < 4; ++r) {
+          keep[r] = __shfl(w1, 4 * c + r);
+          add[r] = __shfl(w2, 4 * c + r);
+        }
+      }
 #pragma unroll
       for (int r = 0; r < 4; ++r) {
         const int h = 4 * c + r;
         if (h < G) {
           f32x4* row = (f32x4*)(rec + h * kHeadDim + 8 * n);
-          row[0] = f32x4{o[0][r], o[1][r], o[2][r], o[3][r]};
-          row[1] = f32x4{o[4][r], o[5][r], o[6][r], o[7][r]};
+          f32x4 r0 = {o[0][r], o[1][r], o[2][r], o[3][r]};
+          f32x4 r1 = {o[4][r], o[5][r], o[6][r], o[7][r]};
+          if (seg_open) {
+            const f32x4 p0 = row[0], p1 = row[1];
+#pragma unroll
+            for (int e = 0; e < 4; ++e) {
+              r0[e] = keep[r] * p0[e] + add[r] * r0[e];
+              r1[e] = keep[r] * p1[e] + add[r] * r1[e];
+            }
+          }
+          row[0] = r0;
+          row[1] = r1;
         }
       }
       if (c == 0) *(f32x2*)(rec + G * kHeadDim + 2 * n) = (n < G) ? f32x2{m, lt} : f32x2{kNegInf, 0.f};
-      rec_slots = (lane == nrec) ? slot : rec_slots;
-      if (++nrec == a.rec_buffered) drain_records();
+      seg_open = true;
       m = kNegInf;
       l = 0.f;
 #pragma unroll
@@ -387,7 +405,7 @@ hipError_t launch_attn_stream(const AttnLaunch& a_in, hipStream_t stream) {
   AttnLaunch a = a_in;
   // LDS per workgroup: the prefix arrays, then as many parked records per
   // wavefront as fit in 64 KiB (at most 8).
-  const size_t cum_bytes = (size_t)((3 * (a.S + 1) + 3) & ~3) * sizeof(int);
+  const size_t cum_bytes = (size_t)((2 * (a.S + 1) + 3) & ~3) * sizeof(int);
   const size_t rec_bytes = (size_t)record_floats(a.G) * sizeof(float);
   const size_t room = (size_t)64 * 1024 - cum_bytes;
   a.rec_buffered = (int)(room / (kStreamWavesPerGroup * rec_bytes));

@@ -47,16 +47,15 @@ int check_shape(const pkv_attn_shape* sh, Geometry* g) {
   const int64_t max_blocks = (max_ctx + pkv::kBlockTokens - 1) / pkv::kBlockTokens;
   if ((int64_t)sh->num_kv_heads * sh->num_seqs * max_blocks > INT32_MAX) return PKV_ERR_SHAPE;
   if ((int64_t)sh->num_seqs * sh->num_q_heads > INT32_MAX) return PKV_ERR_SHAPE;
-  const int64_t NP = (max_ctx + P - 1) / P;
   g->G = G;
   g->P = P;
   g->max_ctx = max_ctx;
-  g->slots = (int64_t)sh->num_kv_heads * sh->num_seqs * NP + pkv::kStreamWaves + 1;
-  if (g->slots > INT32_MAX) return PKV_ERR_SHAPE;
+  // one record per (wavefront, request, KV head) that meet: slot = segment + wavefront
+  g->slots = (int64_t)sh->num_kv_heads * sh->num_seqs + pkv::kStreamWaves;
   return PKV_OK;
 }
 
-// Workspace: the partial records, then the two prefix arrays.
+// Workspace: the partial records, then the prefix array.
 struct WorkspaceLayout {
   size_t rec_bytes, cum_bytes;
   size_t total() const { return rec_bytes + cum_bytes; }
@@ -65,7 +64,7 @@ struct WorkspaceLayout {
 WorkspaceLayout workspace_layout(const pkv_attn_shape* sh, const Geometry& g) {
   WorkspaceLayout w;
   w.rec_bytes = (size_t)g.slots * pkv::record_floats(g.G) * sizeof(float);
-  w.cum_bytes = ((size_t)2 * (sh->num_seqs + 1) * sizeof(int32_t) + 15) & ~(size_t)15;
+  w.cum_bytes = ((size_t)(sh->num_seqs + 1) * sizeof(int32_t) + 15) & ~(size_t)15;
   return w;
 }
 

@@ -35,11 +35,16 @@ constexpr int kStreamWaves = kStreamGroups * kStreamWavesPerGroup;
 //       pos = Hkv * cumB[s] + kvh * nblk_s + b,     cumB[s] = sum_{s'<s} nblk_s'.
 //   Wavefront w owns positions [w*T/W, (w+1)*T/W), T = Hkv * cumB[S].
 //   A run is a maximal stretch of one wavefront's share inside one segment and
-//   one partition (P tokens of the request); every run yields one partial record
-//   (max, sum, un-normalised row) per query head of the group, stored at
-//       slot = Hkv * cumNP[s] + kvh * NP_s + p + w,  NP_s = ceil(L_s/P),
-//   which is unique and increases along the stream, so the records of a segment
-//   are the consecutive slots between its first and its last run.
+//   one partition (P tokens of the request); every run yields one partial result
+//   (max, sum, un-normalised row) per query head of the group.  The runs of one
+//   segment inside one share are folded into one record before it leaves the
+//   wavefront, stored at
+//       slot = s * Hkv + kvh + w,
+//   which is unique and increases along the stream (from one record to the next
+//   the segment, the wavefront or both advance), so the records of a segment are
+//   the consecutive slots from (its index + the owner of its first block) to
+//   (its index + the owner of its last block); slots skipped where a share and a
+//   segment end together belong to nobody and are never read.
 __host__ __device__ inline int64_t share_start(int64_t w, int64_t T, int64_t W) { return w * T / W; }
 // The wavefront whose share holds position pos.
 __host__ __device__ inline int share_owner(int64_t pos, int64_t T, int64_t W) {
@@ -58,7 +63,7 @@ struct AttnLaunch {
   const int32_t* context_lens;
   uint16_t* out;
   float* ws_rec;   // [slots][record_floats(G)] partial records, see record_floats()
-  int32_t* ws_cum; // [2 * (S + 1)]   cumB then cumNP, written by the stream pass for the merge
+  int32_t* ws_cum; // [S + 1] cumB, written by the stream pass for the merge
   float scale_log2e;
   int S, Hq, Hkv, G, MAXB;
   int upb;         // 16-token units per physical block (B / 16)

@@ -42,11 +42,11 @@ def test_partition_and_workspace():
     assert pkv.pkv_attn_partition_size(sh) == 512
     a16 = lambda x: (x + 15) // 16 * 16
     rec = (5 * 128 + 32) * 4             # one record: 5 rows of 128 floats + 16 (max, sum) pairs
-    slots = 8 * 128 * 64 + 2048 + 1      # kv heads x requests x partitions + stream wavefronts + 1
-    assert pkv.pkv_attn_workspace_bytes(sh) == slots * rec + a16(2 * 129 * 4)
-    sh.max_context_len = 512
-    slots = 8 * 128 * 1 + 2048 + 1
-    assert pkv.pkv_attn_workspace_bytes(sh) == slots * rec + a16(2 * 129 * 4)
+    slots = 8 * 128 + 2048               # (request, KV head) segments + stream wavefronts
+    assert pkv.pkv_attn_workspace_bytes(sh) == slots * rec + a16(129 * 4)
+    sh.max_context_len = 512             # neither the bound nor the partition changes the size:
+    sh.partition_size = 16               # runs are folded per (wavefront, segment) before they leave LDS
+    assert pkv.pkv_attn_workspace_bytes(sh) == slots * rec + a16(129 * 4)
     sh = pkv.make_shape(4, 8, 2, 19, 128)
     P = pkv.pkv_attn_partition_size(sh)
     assert P % 16 == 0 and 16 <= P <= 65536
