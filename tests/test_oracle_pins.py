@@ -309,3 +309,91 @@ def test_kv_append_against_indexing():
     for s, L in enumerate(w.context_lens):
         if L > 0:
             assert np.abs(ref[s, 0] - wl.bf16_bits_to_f64(v_new[s, 0])).max() < 1e-6
+
+
+# ---- the comparison every tolerance assertion goes through ------------------------------
+
+def _bits(values):
+    """bf16 bit patterns of values that bf16 holds exactly (checked), via torch."""
+    t = torch.tensor(values, dtype=torch.float64)
+    b = t.to(torch.bfloat16)
+    assert torch.equal(b.to(torch.float64), t), "test values must be exact in bf16"
+    return b.view(torch.int16).numpy().view(np.uint16)
+
+
+def test_compare_known_errors():
+    """Hand-made arrays with errors known in advance."""
+    ref = np.array([[[1.0, 2.0], [3.0, 4.0]],
+                    [[0.5, -0.5], [8.0, -16.0]]])            # [S=2, Hq=2, D=2]
+    exact = oracle.compare(_bits(ref.tolist()), ref)
+    assert exact == {"max_abs": 0.0, "rel_l2": 0.0, "worst_seq_rel_l2": 0.0}
+    # one element of request 0 off by 0.5, one of request 1 off by 0.25
+    got = [[[1.0, 2.5], [3.0, 4.0]], [[0.5, -0.25], [8.0, -16.0]]]
+    c = oracle.compare(_bits(got), ref)
+    assert c["max_abs"] == 0.5
+    # ||diff|| = sqrt(0.25 + 0.0625); ||ref||^2 = 1 + 4 + 9 + 16 + 0.25 + 0.25 + 64 + 256
+    assert c["rel_l2"] == pytest.approx(math.sqrt(0.3125) / math.sqrt(350.5), rel=1e-14)
+    # per request: 0.5 / sqrt(30) against 0.25 / sqrt(320.5): request 0 is the worst
+    assert c["worst_seq_rel_l2"] == pytest.approx(0.5 / math.sqrt(30.0), rel=1e-14)
+    # the same errors the other way round: now request 1 is the worst, and its own norm is used
+    got = [[[1.0, 2.0], [3.0, 4.0]], [[2.5, -0.5], [8.0, -16.0]]]
+    c = oracle.compare(_bits(got), ref)
+    assert c["max_abs"] == 2.0
+    assert c["worst_seq_rel_l2"] == pytest.approx(2.0 / math.sqrt(320.5), rel=1e-14)
+    assert c["rel_l2"] == pytest.approx(2.0 / math.sqrt(350.5), rel=1e-14)
+    # a flat array of bits is read in the reference's row-major order
+    flat = _bits(got).reshape(-1)
+    assert oracle.compare(flat, ref) == c
+    # sign matters: -x against x is an error of 2|x|
+    c = oracle.compare(_bits((-ref).tolist()), ref)
+    assert c["max_abs"] == 32.0 and c["rel_l2"] == pytest.approx(2.0, rel=1e-14)
+
+
+def test_compare_reads_bf16_bit_patterns():
+    ref = np.array([[[1.0, -2.0, 0.0, 0.099609375]]])
+    bits = np.array([[[0x3F80, 0xC000, 0x8000, 0x3DCC]]], dtype=np.uint16)   # 1, -2, -0, 0.099609375
+    assert oracle.compare(bits, ref)["max_abs"] == 0.0
+    bits[0, 0, 3] = 0x3DCD                                    # one unit in the last place up: 2^-11
+    assert oracle.compare(bits, ref)["max_abs"] == 2.0 ** -11
+
+
+def test_compare_zero_reference_and_empty_batch():
+    """A reference that is zero everywhere (requests of length 0) has no relative scale: the
+    measure falls back to the absolute norm of the difference, and rows whose reference is
+    zero take no part in the per-request maximum."""
+    ref = np.zeros((2, 1, 2))
+    assert oracle.compare(_bits([[[0.0, 0.0]], [[0.0, 0.0]]]), ref) == \
+        {"max_abs": 0.0, "rel_l2": 0.0, "worst_seq_rel_l2": 0.0}
+    c = oracle.compare(_bits([[[0.0, 3.0]], [[4.0, 0.0]]]), ref)
+    assert c["max_abs"] == 4.0 and c["rel_l2"] == 5.0 and c["worst_seq_rel_l2"] == 0.0
+    ref = np.array([[[0.0, 0.0]], [[1.0, 1.0]]])
+    c = oracle.compare(_bits([[[0.0, 0.0]], [[1.0, 1.5]]]), ref)
+    assert c["worst_seq_rel_l2"] == pytest.approx(0.5 / math.sqrt(2.0), rel=1e-14)
+    assert oracle.compare(np.zeros((0, 4, 8), np.uint16), np.zeros((0, 4, 8))) == \
+        {"max_abs": 0.0, "rel_l2": 0.0, "worst_seq_rel_l2": 0.0}
+
+
+def test_compare_rejects_wrong_outputs_at_the_bar():
+    """Outputs that are wrong in the ways a kernel can be wrong land above the parity bar
+    (max-abs 1e-2, relative L2 5e-3), and a correctly rounded output lands below it."""
+    w = wl.custom([40, 300, 77], 8, 2, seed=31, num_pool_blocks=64)
+    q, k, v = wl.make_host_tensors(w)
+    ref = oracle.paged_decode_attn(q, k, v, w.block_tables, w.context_lens, w.scale)
+    rounded = torch.from_numpy(ref).to(torch.bfloat16).view(torch.int16).numpy().view(np.uint16)
+    good = oracle.compare(rounded, ref)
+    assert good["max_abs"] <= 1e-2 and 5e-4 < good["rel_l2"] <= 5e-3 and good["worst_seq_rel_l2"] <= 5e-3
+    wrong = {
+        "heads swapped": rounded[:, ::-1, :],
+        "requests rotated": np.roll(rounded, 1, axis=0),
+        "dims reversed": rounded[:, :, ::-1],
+        "truncated instead of rounded, then one ulp low": rounded - np.uint16(1),
+        "one request zero": np.concatenate([rounded[:1] * np.uint16(0), rounded[1:]]),
+    }
+    for what, bits in wrong.items():
+        c = oracle.compare(np.ascontiguousarray(bits), ref)
+        assert c["rel_l2"] > 5e-3 or c["max_abs"] > 1e-2, what
+    # an error confined to the shortest request still shows in the per-request figure
+    bits = rounded.copy()
+    bits[0, 0, :4] ^= np.uint16(0x0040)                       # flips a mantissa bit: ~25-50 % off
+    c = oracle.compare(bits, ref)
+    assert c["worst_seq_rel_l2"] > 5e-3 and c["worst_seq_rel_l2"] > c["rel_l2"]

@@ -323,3 +323,147 @@ def test_invariants_on_random_walks(seed):
             else:
                 kinds.append(po.TOKEN)
         c.commit(i, now, kinds)
+
+
+# ---- queue dynamics: hand-worked tables -------------------------------------------------
+# Every expected value below was worked out on paper from the paper's words: a request that
+# has consumed all of its token quantum loses priority inside its queue and requests take
+# their quanta in circular order (Sections II-B, V-A); under memory pressure the
+# lowest-priority request is the one evicted (Section II-B); a reasoning request is demoted
+# when its KV cache exceeds the threshold (Section IV-C); a_i counts the answering requests
+# that have not yet exhausted their first quantum (Section IV-B).  Nothing here is computed
+# by the code under test.
+
+P, O, G_, F = po.OP_PREFILL, po.OP_OFFLOAD, po.OP_GROW, po.OP_FREE
+
+
+def _one_instance(**kw):
+    base = dict(num_instances=1, gpu_blocks=64, block_tokens=16, quantum=3, demote_tokens=10 ** 9)
+    base.update(kw)
+    return po.Cluster(po.Config(**base))
+
+
+def test_table_quantum_of_three_two_requests():
+    """Quantum 3.  Request 0 arrives one iteration before request 1.  The third token of a
+    quantum exhausts it (not the fourth): the request goes to the back right then."""
+    c = _one_instance()
+    c.submit(16, 0.0)
+    want_batch = [[0], [0, 1], [0, 1], [1, 0], [0, 1], [0, 1], [1, 0]]
+    want_lens = [[16], [17, 16], [18, 17], [18, 19], [20, 19], [21, 20], [21, 22]]
+    want_queue = [[0], [0, 1], [1, 0], [0, 1], [0, 1], [1, 0], [0, 1]]
+    want_quanta = [(0, 0), (0, 0), (1, 0), (1, 1), (1, 1), (2, 1), (2, 2)]   # completed quanta of 0, 1
+    for it in range(7):
+        rids, lens, _ = c.plan(0)
+        assert (rids, lens) == (want_batch[it], want_lens[it]), f"iteration {it + 1}"
+        c.commit(0, 0.1 * (it + 1), [po.TOKEN] * len(rids))
+        assert list(c.inst[0].high) == want_queue[it], f"queue after iteration {it + 1}"
+        assert (c.req[0].quanta_done, c.req[1].quanta_done if len(c.req) > 1 else 0) == want_quanta[it]
+        if it == 0:
+            c.submit(16, 0.1)                       # request 1 arrives after the first iteration
+
+
+def test_table_circular_order_under_a_batch_cap():
+    """One request per iteration, quantum 3: three tokens each, in turn."""
+    c = _one_instance(max_batch=1)
+    c.submit(16, 0.0)
+    c.submit(16, 0.0)
+    ran = []
+    for it in range(12):
+        rids, _, _ = c.plan(0)
+        ran += rids
+        c.commit(0, 0.1 * (it + 1), [po.TOKEN] * len(rids))
+    assert ran == [0, 0, 0, 1, 1, 1, 0, 0, 0, 1, 1, 1]
+
+
+def test_table_demotion_needs_more_than_the_threshold():
+    """Threshold 20 tokens, prompt 18: still high-priority with exactly 20 tokens of KV cache,
+    demoted by the token that makes it 21, in that very iteration."""
+    c = _one_instance(quantum=500, demote_tokens=20)
+    c.submit(18, 0.0)
+    levels, kv = [], []
+    for it in range(5):
+        rids, lens, _ = c.plan(0)
+        assert rids == [0]
+        c.commit(0, 0.1 * (it + 1), [po.TOKEN])
+        levels.append(c.req[0].level)
+        kv.append(c.req[0].kv_tokens)
+    assert kv == [18, 19, 20, 21, 22]
+    assert levels == [po.HIGH, po.HIGH, po.HIGH, po.LOW, po.LOW]
+    assert list(c.inst[0].high) == [] and list(c.inst[0].low) == [0]
+    assert c.req[0].phase == po.REASONING          # still reasoning, only treated as low priority
+    assert c.r(0) == 0                              # and no longer counted among the reasoning requests
+
+
+def test_table_victim_is_the_last_in_order():
+    """Three requests of one block each fill a three-block instance.  When the first needs a
+    second block, the request at the END of the round-robin order is evicted (request 2), not the
+    one right behind it (request 1); request 1 then finds no block either and waits, resident."""
+    c = _one_instance(gpu_blocks=3, quantum=500)
+    for _ in range(3):
+        c.submit(16, 0.0)
+    rids, lens, ops = c.plan(0)
+    assert (rids, lens) == ([0, 1, 2], [16, 16, 16])
+    assert ops == [(P, 0, 0, (0,), -1, ()), (P, 0, 1, (1,), -1, ()), (P, 0, 2, (2,), -1, ())]
+    c.commit(0, 0.1, [po.TOKEN] * 3)
+    rids, lens, ops = c.plan(0)
+    assert (rids, lens) == ([0], [17])
+    assert ops == [(O, 0, 2, (2,), -1, ()), (G_, 0, 0, (2,), -1, ())]
+    assert [c.req[r].state for r in range(3)] == [po.RESIDENT, po.RESIDENT, po.OFFLOADED]
+    assert (c.req[2].preemptions, c.req[2].offloaded_blocks, c.req[1].preemptions) == (1, 1, 0)
+    c.commit(0, 0.2, [po.TOKEN])
+    rids, lens, ops = c.plan(0)                    # nothing changes hands: 1 and 2 keep waiting
+    assert (rids, lens, ops) == ([0], [18], [])
+    c.commit(0, 0.3, [po.TOKEN])
+
+
+def test_table_victim_follows_round_robin_order_not_arrival():
+    """Quantum 2.  Request 0 arrives first and uses up its quantum, which puts it behind 1 and
+    2; when memory runs out it is request 0 that goes, although it is the oldest."""
+    c = _one_instance(gpu_blocks=4, quantum=2)
+    c.submit(16, 0.0)
+    assert c.plan(0) == ([0], [16], [(P, 0, 0, (0,), -1, ())])
+    c.commit(0, 0.1, [po.TOKEN])
+    c.submit(16, 0.1)
+    c.submit(16, 0.1)
+    rids, lens, ops = c.plan(0)
+    assert (rids, lens) == ([0, 1, 2], [17, 16, 16])
+    assert ops == [(G_, 0, 0, (1,), -1, ()), (P, 0, 1, (2,), -1, ()), (P, 0, 2, (3,), -1, ())]
+    c.commit(0, 0.2, [po.TOKEN] * 3)
+    assert list(c.inst[0].high) == [1, 2, 0]       # 0 has had its two tokens
+    rids, lens, ops = c.plan(0)
+    assert (rids, lens) == ([1, 2], [17, 17])
+    assert [(op[0], op[2]) for op in ops] == [(O, 0), (G_, 1), (G_, 2)]
+    assert ops[0][3] == (0, 1)                      # both of request 0's blocks are given up
+    assert sorted(ops[1][3] + ops[2][3]) == [0, 1]  # and handed to 1 and 2
+    assert c.req[0].state == po.OFFLOADED
+
+
+def test_table_fresh_answering_requests():
+    """a_i: answering requests that have not used up their first quantum (3 tokens here)."""
+    c = _one_instance()
+    c.submit(16, 0.0)
+    now = 0.0
+
+    def step(kinds):
+        nonlocal now
+        rids, _, _ = c.plan(0)
+        now += 0.1
+        c.commit(0, now, [kinds.get(r, po.TOKEN) for r in rids])
+        return rids
+
+    step({})                                        # prefill: first reasoning token
+    assert (c.r(0), c.a(0)) == (1, 0)
+    step({0: po.END_OF_REASONING})                  # the closing token of the reasoning phase
+    assert (c.r(0), c.a(0)) == (0, 1) and list(c.inst[0].low) == [0]
+    step({}); assert c.a(0) == 1                    # 1st answering token
+    step({}); assert c.a(0) == 1                    # 2nd
+    step({}); assert c.a(0) == 0                    # 3rd: first quantum exhausted
+    assert len(c.req[0].answer_times) == 3
+    c.submit(16, now)                               # a newcomer reasons for two iterations ...
+    assert (c.r(0), c.a(0)) == (1, 0)
+    assert step({}) == [1, 0]                       # reasoning runs ahead of answering
+    step({1: po.END_OF_REASONING})
+    assert (c.r(0), c.a(0)) == (0, 1)               # ... and is the only fresh answering request
+    assert list(c.inst[0].low) == [0, 1]
+    step({}); step({}); assert c.a(0) == 1
+    step({}); assert c.a(0) == 0
