@@ -135,6 +135,29 @@ int paged_decode_attn_layers(const void* const* q, const void* const* k_pools,
                              size_t workspace_bytes, void* stream);
 
 /*
+ * paged_decode_attn for callers that cannot allocate device memory or carry a
+ * workspace around: code under HIP graph capture, tight serving loops, harnesses
+ * that forbid hipMalloc.  Same arguments, same kernels and bit-identical results,
+ * but the workspace is a fixed array of PKV_STATIC_WORKSPACE_BYTES that every
+ * GPU the library runs on holds from load time until the process ends.  The
+ * call allocates and frees nothing (no hipMalloc, no hipFree, no allocating
+ * library routine); the first call on a device looks the array's address up
+ * and should therefore be made once outside a graph capture.
+ *
+ * Returns PKV_ERR_WORKSPACE, enqueuing nothing, when pkv_attn_workspace_bytes()
+ * for `shape` exceeds PKV_STATIC_WORKSPACE_BYTES (set max_context_len to the
+ * batch's longest context to keep the bound tight).  All calls on one GPU share
+ * the one array: two calls of this entry point that overlap in time on the same
+ * GPU (different streams, or graphs replayed concurrently) race and give
+ * undefined rows.  The array's contents need no initialisation between calls
+ * and are undefined afterwards.
+ */
+#define PKV_STATIC_WORKSPACE_BYTES (32u << 20)
+int paged_decode_attn_static(const void* q, const void* k_pool, const void* v_pool,
+                             const int32_t* block_tables, const int32_t* context_lens,
+                             float scale, void* out, const pkv_attn_shape* shape, void* stream);
+
+/*
  * staging[i] = pool[block_ids[i]] for i in [0, n_blocks): the send side of
  * evicting a preempted request's KV cache (paper Section II-B) or of shipping
  * a request's entire KV cache at the reasoning-to-answering transition

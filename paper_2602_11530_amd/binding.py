@@ -24,7 +24,7 @@ PKV_ERR_HOST = -6
 
 EXPORTS = (
     "pkv_attn_partition_size", "pkv_attn_workspace_bytes", "paged_decode_attn",
-    "paged_decode_attn_layers",
+    "paged_decode_attn_layers", "paged_decode_attn_static",
     "kv_blocks_gather", "kv_blocks_scatter", "kv_blocks_move", "kv_blocks_offload", "kv_blocks_reload",
     "kv_append", "pkv_status_string",
     "pkv_last_launch_error", "pkv_version",
@@ -81,6 +81,8 @@ def lib() -> ctypes.CDLL:
         L.paged_decode_attn.argtypes = [vp, vp, vp, i32p, i32p, ctypes.c_float, vp, shp, vp,
                                         ctypes.c_size_t, vp]
         L.paged_decode_attn.restype = ctypes.c_int
+        L.paged_decode_attn_static.argtypes = [vp, vp, vp, i32p, i32p, ctypes.c_float, vp, shp, vp]
+        L.paged_decode_attn_static.restype = ctypes.c_int
         L.paged_decode_attn_layers.argtypes = [vp, vp, vp, i32p, i32p, ctypes.c_float, vp,
                                                ctypes.c_int32, shp, vp, ctypes.c_size_t, vp]
         L.paged_decode_attn_layers.restype = ctypes.c_int
@@ -152,6 +154,17 @@ def paged_decode_attn(q, k_pool, v_pool, block_tables, context_lens, scale, out,
                                    _ptr(context_lens), ctypes.c_float(scale), _ptr(out),
                                    ctypes.byref(shape), _ptr(workspace), ws_bytes,
                                    _stream(stream)))
+
+
+STATIC_WORKSPACE_BYTES = 32 << 20
+
+
+def paged_decode_attn_static(q, k_pool, v_pool, block_tables, context_lens, scale, out,
+                             shape: AttnShape, stream=None) -> None:
+    """The same call on the library's own fixed workspace: allocates nothing."""
+    _check(lib().paged_decode_attn_static(_ptr(q), _ptr(k_pool), _ptr(v_pool), _ptr(block_tables),
+                                          _ptr(context_lens), ctypes.c_float(scale), _ptr(out),
+                                          ctypes.byref(shape), _stream(stream)))
 
 
 def pointer_array(tensors):

@@ -4,6 +4,15 @@
 
 #include "pkv_kernels.h"
 
+#include <atomic>
+
+// Workspace of paged_decode_attn_static: device memory that exists from the
+// moment the library is loaded on a GPU until the process ends, so that entry
+// point never allocates.  In host code this name is only a handle for
+// hipGetSymbolAddress; the address kernels are given is looked up per device.
+constexpr size_t kStaticScratchBytes = PKV_STATIC_WORKSPACE_BYTES;
+static __device__ __align__(256) unsigned char scratch[kStaticScratchBytes];
+
 namespace {
 
 thread_local hipError_t g_last_launch_error = hipSuccess;
@@ -76,6 +85,27 @@ int launch_status(hipError_t e) {
   if (e == hipSuccess) return PKV_OK;
   g_last_launch_error = e;
   return PKV_ERR_LAUNCH;
+}
+
+// Every GPU holds its own copy of `scratch` at its own address; the address is
+// looked up once per device, with that device current, and kept.
+constexpr int kMaxDevices = 64;
+std::atomic<void*> g_scratch_ptr[kMaxDevices];
+
+int static_scratch(void** out) {
+  int dev = -1;
+  hipError_t e = hipGetDevice(&dev);
+  if (e != hipSuccess) return launch_status(e);
+  if (dev < 0 || dev >= kMaxDevices) return launch_status(hipErrorInvalidDevice);
+  void* p = g_scratch_ptr[dev].load(std::memory_order_acquire);
+  if (!p) {
+    e = hipGetSymbolAddress(&p, HIP_SYMBOL(scratch));
+    if (e != hipSuccess) return launch_status(e);
+    if (!p) return launch_status(hipErrorInvalidSymbol);
+    g_scratch_ptr[dev].store(p, std::memory_order_release);
+  }
+  *out = p;
+  return PKV_OK;
 }
 
 }  // namespace
@@ -182,6 +212,26 @@ int paged_decode_attn(const void* q, const void* k_pool, const void* v_pool,
   if (rc != PKV_OK || empty) return rc;
   rc = check_layer_pointers(q, k_pool, v_pool, out);
   if (rc != PKV_OK) return rc;
+  return launch_layer(a, q, k_pool, v_pool, out, static_cast<hipStream_t>(stream));
+}
+
+int paged_decode_attn_static(const void* q, const void* k_pool, const void* v_pool,
+                             const int32_t* block_tables, const int32_t* context_lens, float scale,
+                             void* out, const pkv_attn_shape* shape, void* stream) {
+  Geometry g;
+  int rc = check_shape(shape, &g);
+  if (rc != PKV_OK) return rc;
+  if (shape->num_seqs == 0) return PKV_OK;
+  if (workspace_bytes(shape, g) > kStaticScratchBytes) return PKV_ERR_WORKSPACE;
+  rc = check_layer_pointers(q, k_pool, v_pool, out);
+  if (rc != PKV_OK) return rc;
+  void* ws = nullptr;
+  rc = static_scratch(&ws);
+  if (rc != PKV_OK) return rc;
+  pkv::AttnLaunch a;
+  bool empty = false;
+  rc = prepare_attn(block_tables, context_lens, scale, shape, ws, kStaticScratchBytes, &a, &empty);
+  if (rc != PKV_OK || empty) return rc;
   return launch_layer(a, q, k_pool, v_pool, out, static_cast<hipStream_t>(stream));
 }
 
