@@ -13,9 +13,14 @@
  *     bf16 [num_pool_blocks][num_kv_heads][block_size][head_dim], row-major,
  * so one physical block is one contiguous image of
  *     num_kv_heads * block_size * head_dim * 2 bytes  (32 KiB at 8 x 16 x 128).
- * block_size is 16, 32 or 64 tokens; head_dim is 128.
+ * block_size is 16, 32 or 64 tokens; head_dim is 64, 128 or 256.
  *
- * Status codes: 0 = PKV_OK; negative = error, nothing was enqueued.
+ * Status codes: 0 = PKV_OK; negative = error.  Every argument error (NULL,
+ * SHAPE, ALIGN, WORKSPACE, HOST) is found before the first launch and enqueues
+ * nothing.  PKV_ERR_LAUNCH means HIP refused a launch or a copy part-way: what
+ * the call had enqueued before (an earlier layer of paged_decode_attn_layers,
+ * the stream pass of an attention call, the first half of an offload or reload)
+ * stays enqueued, and the outputs of that call are undefined.
  */
 #ifndef PKV_H_
 #define PKV_H_
@@ -43,7 +48,7 @@ typedef struct {
   int32_t num_q_heads;        /* Hq                                                      */
   int32_t num_kv_heads;       /* Hkv; Hq % Hkv == 0; query heads h*G..h*G+G-1 share
                                  KV head h (G = Hq/Hkv, 1 <= G <= 16)                    */
-  int32_t head_dim;           /* D: 128                                                  */
+  int32_t head_dim;           /* D: 64, 128 or 256 (256 only with G <= 8)                */
   int32_t block_size;         /* B: tokens per physical block: 16, 32 or 64              */
   int32_t max_blocks_per_seq; /* MAXB: row stride of block_tables, >= ceil(L_s/B)        */
   int32_t partition_size;     /* P: split-K partition, the most tokens of a request that
@@ -258,6 +263,25 @@ int kv_blocks_reload(const void* host_src, void* staging, void* pool, const int3
 int kv_append(const void* k_new, const void* v_new, void* k_pool, void* v_pool,
               const int32_t* block_tables, const int32_t* context_lens,
               const pkv_attn_shape* shape, void* stream);
+
+/*
+ * Optional report of block ids the kernels refused to follow.  No kernel of this
+ * library ever dereferences a block id outside its pool: attention leaves the
+ * tokens of such a block out, the copies and kv_append skip the entry.  That
+ * keeps a corrupt table from becoming a memory fault, but it also means a request
+ * can silently lose part of its KV cache (the whole-cache transfer of Section
+ * IV-B is then no longer exact).  After this call, every call made by the calling
+ * thread adds to *device_counter, on the device and in stream order, the number of
+ * refused entries it met: one per skipped list entry of a copy or move, one per
+ * skipped request of kv_append, one per refused 16-token unit and KV head in
+ * attention (so any non-zero value means "a block id was out of range").
+ *
+ *   device_counter  device int32, 4-byte aligned, owned, zeroed and read by the
+ *                   caller; it must stay valid while calls of this thread may
+ *                   still run.  NULL (the initial state) switches the report off.
+ * Returns PKV_OK, or PKV_ERR_ALIGN.  Allocates nothing, launches nothing.
+ */
+int pkv_set_id_fault_counter(int32_t* device_counter);
 
 /* Static text for a status code. */
 const char* pkv_status_string(int status);

@@ -26,7 +26,7 @@ EXPORTS = (
     "pkv_attn_partition_size", "pkv_attn_workspace_bytes", "paged_decode_attn",
     "paged_decode_attn_layers", "paged_decode_attn_static",
     "kv_blocks_gather", "kv_blocks_scatter", "kv_blocks_move", "kv_blocks_offload", "kv_blocks_reload",
-    "kv_append", "pkv_status_string",
+    "kv_append", "pkv_set_id_fault_counter", "pkv_status_string",
     "pkv_last_launch_error", "pkv_version",
 )
 
@@ -96,6 +96,8 @@ def lib() -> ctypes.CDLL:
         L.kv_blocks_offload.restype = ctypes.c_int
         L.kv_blocks_reload.argtypes = [vp, vp, vp, i32p, i64, i64, i64, vp]
         L.kv_blocks_reload.restype = ctypes.c_int
+        L.pkv_set_id_fault_counter.argtypes = [vp]
+        L.pkv_set_id_fault_counter.restype = ctypes.c_int
         L.kv_append.argtypes = [vp, vp, vp, vp, i32p, i32p, shp, vp]
         L.kv_append.restype = ctypes.c_int
         _lib = L
@@ -121,6 +123,12 @@ def _stream(stream) -> Optional[int]:
         stream = torch.cuda.current_stream()
     h = int(getattr(stream, "cuda_stream", stream))
     return h or None
+
+
+def pkv_set_id_fault_counter(counter) -> None:
+    """``counter``: a one-element int32 device tensor that later calls of this thread add the
+    number of refused block ids to, or None to switch the report off."""
+    _check(lib().pkv_set_id_fault_counter(_ptr(counter)))
 
 
 def pkv_version() -> int:

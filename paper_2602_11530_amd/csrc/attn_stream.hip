@@ -13,8 +13,8 @@
 // LDS, and writes one record per (wavefront, request, KV head); the merge pass
 // combines the records of each (request, query head).
 //
-// Per 16-token block, lane = 16*c + n:
-//   S^T = K . Q^T   four v_mfma_f32_16x16x32_bf16 (k = 32 dims each).
+// Per 16-token block, lane = 16*c + n, head_dim D = 128 (64 and 256 below):
+//   S^T = K . Q^T   D/32 v_mfma_f32_16x16x32_bf16 (k = 32 dims each).
 //         A = K rows: lane (n, c) loads the 16 bytes at dims 32*jj + 8*c of
 //         token tau(n) = 4*(n%4) + n/4, straight from the pool (a 64-byte run
 //         per token per load).  B = q: lane (n, c) holds the same dims of head n
@@ -22,12 +22,19 @@
 //         with head n's scores for tokens 4*i + c.
 //   P     = exp2(score - m) in fp32, split into bf16 hi + lo parts so that the
 //         weights keep ~16 mantissa bits through the second product.
-//   O    += P . V   eight v_mfma_f32_16x16x16_bf16 per part.  V is loaded in its
+//   O    += P . V   D/16 v_mfma_f32_16x16x16_bf16 per part.  V is loaded in its
 //         natural order (lane (n, c) gets dims 8n..8n+7 of tokens 4*e + c, four
 //         fully contiguous 1 KiB loads); the operand for output dims 8*n + i
 //         pairs up the i-th halves of those four loads with v_perm_b32.  The
 //         token order 4*e + c is exactly the one the scores came out in, so P
 //         needs no shuffle between the two products.
+//   D = 64:  lane (n, c) owns dims 4n..4n+3; its V loads are 8 bytes wide (four
+//         fully contiguous 512-byte loads), two K steps, four output tiles, and a
+//         ring twice as deep since a block is half as many bytes.
+//   D = 256: lane (n, c) owns dims 8n..8n+7 of each 128-dim half; eight K steps,
+//         eight 16-byte V loads (a 256-byte run per token per load), sixteen
+//         output tiles; a block is 16 KiB here, and the registers of a ring of four
+//         leave room for one wavefront per SIMD, so half as many wavefronts stream.
 // The running maximum m is only raised when a score exceeds it by more than
 // 2^kLazyLog2; any reference value gives the same softmax, and the bound keeps
 // every weight within fp32/bf16 range.
@@ -48,12 +55,29 @@
 namespace pkv {
 namespace {
 
-#ifndef PKV_RING
-#define PKV_RING 4
-#endif
-constexpr int kRing = PKV_RING;   // 16-token blocks in flight per wavefront (register ring)
 constexpr int kWindow = 64;       // descriptors per window: one per lane
-static_assert(kWindow % kRing == 0, "the window must be a whole number of ring turns");
+
+// What depends on the head dimension.  kRing: 16-token blocks in flight per
+// wavefront plus the one being consumed (a ring of register buffers).
+template <int kD> struct Dim;
+template <> struct Dim<64> {
+  static constexpr int kKSteps = 2, kVLoads = 4, kTiles = 4, kRing = 8;
+  typedef uint32_t VReg __attribute__((ext_vector_type(2)));
+};
+template <> struct Dim<128> {
+  static constexpr int kKSteps = 4, kVLoads = 4, kTiles = 8, kRing = 4;
+  typedef uint32_t VReg __attribute__((ext_vector_type(4)));
+};
+template <> struct Dim<256> {
+  static constexpr int kKSteps = 8, kVLoads = 8, kTiles = 16, kRing = 4;
+  typedef uint32_t VReg __attribute__((ext_vector_type(4)));
+};
+// First dim of output tiles 4t..4t+3 (they are consecutive dims) in the lane of column n.
+template <int kD> __device__ __forceinline__ int tile_group_dim(int t, int n) {
+  if (kD == 64) return 4 * n;
+  if (kD == 128) return 8 * n + 4 * t;
+  return 128 * (t >> 1) + 8 * n + 4 * (t & 1);
+}
 constexpr float kNegInf = -__builtin_huge_valf();
 constexpr float kLazyLog2 = 8.f;
 
@@ -100,12 +124,17 @@ struct Window {
 constexpr int kMetaLast = 1 << 8;
 constexpr int kMetaSegFirst = 1 << 9;
 
+template <int kD>
 __global__ __launch_bounds__(kStreamWavesPerGroup * 64) void attn_stream_kernel(AttnLaunch a) {
+  typedef Dim<kD> DD;
+  typedef typename DD::VReg VReg;
+  constexpr int kKSteps = DD::kKSteps, kVLoads = DD::kVLoads, kTiles = DD::kTiles, kRing = DD::kRing;
+  static_assert(kWindow % kRing == 0, "the window must be a whole number of ring turns");
   extern __shared__ int smem[];
   int* cumB = smem;                  // [S+1] blocks before request s
   int* lens = smem + (a.S + 1);      // [S]   clamped context lengths
   // then room for rec_buffered finished records per wavefront, 16-byte aligned
-  const int rec_floats = record_floats(a.G);
+  const int rec_floats = record_floats(a.G, kD);
   float* rec_stage = (float*)(smem + ((2 * (a.S + 1) + 3) & ~3)) +
                      (threadIdx.x >> 6) * a.rec_buffered * rec_floats;
 
@@ -141,7 +170,7 @@ __global__ __launch_bounds__(kStreamWavesPerGroup * 64) void attn_stream_kernel(
   // Every participating wavefront gets at least one block, so that consecutive
   // runs of a segment always belong to the same or to adjacent wavefronts.
   const int64_t T = (int64_t)Hkv * cumB[S];
-  const int W = (int)min((int64_t)kStreamWaves, T);
+  const int W = (int)min((int64_t)a.waves, T);
   const int w = blockIdx.x * kStreamWavesPerGroup + wave;
   if (w >= W) return;
   const int pos0 = (int)share_start(w, T, W);
@@ -150,6 +179,7 @@ __global__ __launch_bounds__(kStreamWavesPerGroup * 64) void attn_stream_kernel(
   // Descriptors of stream indices jb .. jb+63 of this share.
   int search_steps = 0;
   while ((1 << search_steps) < S) ++search_steps;
+  int refused = 0;   // table entries outside the pool met while describing this share
   auto describe = [&](int jb) -> Window {
     const int j = jb + lane;
     const bool live = j < nshare;
@@ -170,6 +200,7 @@ __global__ __launch_bounds__(kStreamWavesPerGroup * 64) void attn_stream_kernel(
     const int id = live ? a.block_tables[(int64_t)s * a.MAXB + tb] : -1;
     const bool mapped = (unsigned)id < (unsigned)a.NB;   // ids outside the pool are never followed
     if (!mapped) ntok = 0;
+    refused += __popcll(__ballot(live && !mapped));
     Window d;
     d.slab = mapped ? (id * Hkv + kvh) * a.upb + (b - tb * a.upb) : 0;
     const bool last = (b + 1 == nb) || ((b + 1) % bpp == 0) || (j + 1 == nshare);
@@ -184,23 +215,25 @@ __global__ __launch_bounds__(kStreamWavesPerGroup * 64) void attn_stream_kernel(
   Window dB = dA;   // described after the first KV loads are on their way (below)
   int jbase = 0;
 
-  const int64_t head_elems = (int64_t)kBlockTokens * kHeadDim;  // one (block, KV head) slab
+  const int64_t head_elems = (int64_t)kBlockTokens * kD;  // one (block, KV head) slab
   const int tau = 4 * (n & 3) + (n >> 2);
-  const int koff = tau * 16 + c;   // in 16-byte units within the slab
+  const int koff = tau * (kD / 8) + c;   // in 16-byte units within the slab
+  // V, in units of one VReg: token 4*e + c, this lane's dims (of half h when D = 256)
+  const int voff = kD == 256 ? 32 * c + n : lane;
 
-  u32x4 qop[4];        // q as the B operand: dims 32*jj + 8*c .. +7 of head n; zero rows beyond the group
+  u32x4 qop[kKSteps];  // q as the B operand: dims 32*jj + 8*c .. +7 of head n; zero rows beyond the group
   float m = kNegInf;   // running reference maximum of head n (log2 units), same in all four c groups
   float l = 0.f;       // this lane's share of the softmax denominator
-  f32x4 o[8];          // o[i][r]: head 4*c + r, dim 8*n + i
+  f32x4 o[kTiles];     // o[i][r]: head 4*c + r, dim tile_group_dim(i / 4, n) + i % 4
 #pragma unroll
-  for (int i = 0; i < 8; ++i) o[i] = f32x4{0.f, 0.f, 0.f, 0.f};
+  for (int i = 0; i < kTiles; ++i) o[i] = f32x4{0.f, 0.f, 0.f, 0.f};
 
-  // Issue the eight 16-byte loads of stream index j (K in operand order, V
+  // Issue the loads of stream index j (K in operand order, V
   // natural), nontemporal: the stream is read once and must not allocate in the
   // caches it passes through.  The loads are unconditional so that every wait in the loop knows
   // exactly how many are outstanding: a block that is unmapped, or an index past
   // the share's end, reads slab 0 (which always exists) and is masked or skipped.
-  auto issue = [&](u32x4 (&k)[4], u32x4 (&v)[4], int j) {
+  auto issue = [&](u32x4 (&k)[kKSteps], VReg (&v)[kVLoads], int j) {
     const int idx = j - jbase;   // 0 .. 2*kWindow-1
     const int sa = __builtin_amdgcn_readlane(dA.slab, idx & (kWindow - 1));
     const int sb = __builtin_amdgcn_readlane(dB.slab, idx & (kWindow - 1));
@@ -208,11 +241,19 @@ __global__ __launch_bounds__(kStreamWavesPerGroup * 64) void attn_stream_kernel(
     if (j >= nshare) slab = 0;
     const int64_t base = (int64_t)slab * head_elems;
     const u32x4* kp = (const u32x4*)(a.k_pool + base) + koff;
-    const u32x4* vp = (const u32x4*)(a.v_pool + base) + lane;
+    const VReg* vp = (const VReg*)(a.v_pool + base) + voff;
 #pragma unroll
-    for (int jj = 0; jj < 4; ++jj) k[jj] = __builtin_nontemporal_load(kp + 4 * jj);
+    for (int jj = 0; jj < kKSteps; ++jj) k[jj] = __builtin_nontemporal_load(kp + 4 * jj);
+    if (kD == 256) {
 #pragma unroll
-    for (int jj = 0; jj < 4; ++jj) v[jj] = __builtin_nontemporal_load(vp + 64 * jj);
+      for (int e = 0; e < 4; ++e) {
+        v[2 * e] = __builtin_nontemporal_load(vp + 128 * e);
+        v[2 * e + 1] = __builtin_nontemporal_load(vp + 128 * e + 16);
+      }
+    } else {
+#pragma unroll
+      for (int e = 0; e < 4; ++e) v[e] = __builtin_nontemporal_load(vp + 64 * e);
+    }
   };
 
   // Finished records wait in LDS and go out several at a time, with full-width
@@ -234,7 +275,7 @@ __global__ __launch_bounds__(kStreamWavesPerGroup * 64) void attn_stream_kernel(
     nrec = 0;
   };
 
-  auto consume = [&](u32x4 (&k)[4], u32x4 (&v)[4], int j) {
+  auto consume = [&](u32x4 (&k)[kKSteps], VReg (&v)[kVLoads], int j) {
     const int idx = j - jbase;   // always inside window A
     const int meta = __builtin_amdgcn_readlane(dA.meta, idx);
     const int ntok = meta & 0xff;
@@ -243,9 +284,9 @@ __global__ __launch_bounds__(kStreamWavesPerGroup * 64) void attn_stream_kernel(
       // A new (request, KV head): fetch its query group.
       seg_open = false;
       const int qrow = __builtin_amdgcn_readlane(dA.qrow, idx);
-      const u32x4* qp = (const u32x4*)(a.q + (int64_t)(qrow + min(n, G - 1)) * kHeadDim) + c;
+      const u32x4* qp = (const u32x4*)(a.q + (int64_t)(qrow + min(n, G - 1)) * kD) + c;
 #pragma unroll
-      for (int jj = 0; jj < 4; ++jj) {
+      for (int jj = 0; jj < kKSteps; ++jj) {
         const u32x4 wq = qp[4 * jj];
         qop[jj] = (n < G) ? wq : u32x4{0, 0, 0, 0};
       }
@@ -253,7 +294,7 @@ __global__ __launch_bounds__(kStreamWavesPerGroup * 64) void attn_stream_kernel(
 
     f32x4 sc = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
-    for (int jj = 0; jj < 4; ++jj)
+    for (int jj = 0; jj < kKSteps; ++jj)
       sc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, k[jj]),
                                                    __builtin_bit_cast(bf16x8, qop[jj]), sc, 0, 0, 0);
     float x[4] = {sc.x * a.scale_log2e, sc.y * a.scale_log2e, sc.z * a.scale_log2e,
@@ -268,7 +309,10 @@ __global__ __launch_bounds__(kStreamWavesPerGroup * 64) void attn_stream_kernel(
       for (int e = 0; e < 4; ++e) {
         valid[e] = 4 * e + c < ntok;
         x[e] = valid[e] ? x[e] : kNegInf;
-        if (!valid[e]) v[e] = u32x4{0, 0, 0, 0};
+        if (!valid[e]) {
+          if (kD == 256) { v[2 * e] = VReg{}; v[2 * e + 1] = VReg{}; }
+          else v[e] = VReg{};
+        }
       }
     }
     const float mx = fmaxf(fmaxf(x[0], x[1]), fmaxf(x[2], x[3]));
@@ -282,7 +326,7 @@ __global__ __launch_bounds__(kStreamWavesPerGroup * 64) void attn_stream_kernel(
 #pragma unroll
       for (int r = 0; r < 4; ++r) ar[r] = __shfl(alpha, 4 * c + r);
 #pragma unroll
-      for (int i = 0; i < 8; ++i) {
+      for (int i = 0; i < kTiles; ++i) {
         o[i].x *= ar[0]; o[i].y *= ar[1]; o[i].z *= ar[2]; o[i].w *= ar[3];
       }
       m = mnew;
@@ -306,11 +350,13 @@ __global__ __launch_bounds__(kStreamWavesPerGroup * 64) void attn_stream_kernel(
     const s16x4 pa = __builtin_bit_cast(s16x4, phi);
     const s16x4 pb = __builtin_bit_cast(s16x4, plo);
 #pragma unroll
-    for (int i = 0; i < 8; ++i) {
-      const int wsel = i >> 1;
+    for (int i = 0; i < kTiles; ++i) {
+      // tile i needs, for tokens 4*e + c (e = 0..3), the bf16 of its dim: half (i & 1) of
+      // word ((i % 8) >> 1) of the load that holds token e (and, for D = 256, half i / 8)
+      const int wsel = (i & 7) >> 1, h = kD == 256 ? i >> 3 : 0, st = kD == 256 ? 2 : 1;
       const uint32_t sel = (i & 1) ? 0x07060302u : 0x05040100u;
-      const u32x2 vb = {__builtin_amdgcn_perm(v[1][wsel], v[0][wsel], sel),
-                        __builtin_amdgcn_perm(v[3][wsel], v[2][wsel], sel)};
+      const u32x2 vb = {__builtin_amdgcn_perm(v[st + h][wsel], v[h][wsel], sel),
+                        __builtin_amdgcn_perm(v[3 * st + h][wsel], v[2 * st + h][wsel], sel)};
       const s16x4 vop = __builtin_bit_cast(s16x4, vb);
       o[i] = __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(pa, vop, o[i], 0, 0, 0);
       o[i] = __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(pb, vop, o[i], 0, 0, 0);
@@ -335,11 +381,11 @@ __global__ __launch_bounds__(kStreamWavesPerGroup * 64) void attn_stream_kernel(
       if (seg_open) {
         // parked (m1, l1, rows1) and this run's (m, lt, o): weights 2^(m1-M) and 2^(m-M),
         // a side whose maximum is -inf (nothing valid seen) gets weight 0 by select
-        const f32x2 st = *(const f32x2*)(rec + G * kHeadDim + 2 * n);
-        const float M = fmaxf(st.x, m);
-        const float w1 = (st.x == kNegInf) ? 0.f : __builtin_amdgcn_exp2f(st.x - M);
+        const f32x2 ml = *(const f32x2*)(rec + G * kD + 2 * n);
+        const float M = fmaxf(ml.x, m);
+        const float w1 = (ml.x == kNegInf) ? 0.f : __builtin_amdgcn_exp2f(ml.x - M);
         const float w2 = (m == kNegInf) ? 0.f : __builtin_amdgcn_exp2f(m - M);
-        lt = w1 * st.y + w2 * lt;
+        lt = w1 * ml.y + w2 * lt;
         m = M;
 #pragma unroll
         for (int r = 0; r < 4; ++r) {
@@ -351,33 +397,32 @@ __global__ __launch_bounds__(kStreamWavesPerGroup * 64) void attn_stream_kernel(
       for (int r = 0; r < 4; ++r) {
         const int h = 4 * c + r;
         if (h < G) {
-          f32x4* row = (f32x4*)(rec + h * kHeadDim + 8 * n);
-          f32x4 r0 = {o[0][r], o[1][r], o[2][r], o[3][r]};
-          f32x4 r1 = {o[4][r], o[5][r], o[6][r], o[7][r]};
-          if (seg_open) {
-            const f32x4 p0 = row[0], p1 = row[1];
 #pragma unroll
-            for (int e = 0; e < 4; ++e) {
-              r0[e] = keep[r] * p0[e] + add[r] * r0[e];
-              r1[e] = keep[r] * p1[e] + add[r] * r1[e];
+          for (int t = 0; t < kTiles / 4; ++t) {
+            f32x4* dst = (f32x4*)(rec + h * kD + tile_group_dim<kD>(t, n));
+            f32x4 x4 = {o[4 * t][r], o[4 * t + 1][r], o[4 * t + 2][r], o[4 * t + 3][r]};
+            if (seg_open) {
+              const f32x4 p4 = *dst;
+#pragma unroll
+              for (int e = 0; e < 4; ++e) x4[e] = keep[r] * p4[e] + add[r] * x4[e];
             }
+            *dst = x4;
           }
-          row[0] = r0;
-          row[1] = r1;
         }
       }
-      if (c == 0) *(f32x2*)(rec + G * kHeadDim + 2 * n) = (n < G) ? f32x2{m, lt} : f32x2{kNegInf, 0.f};
+      if (c == 0) *(f32x2*)(rec + G * kD + 2 * n) = (n < G) ? f32x2{m, lt} : f32x2{kNegInf, 0.f};
       seg_open = true;
       m = kNegInf;
       l = 0.f;
 #pragma unroll
-      for (int i = 0; i < 8; ++i) o[i] = f32x4{0.f, 0.f, 0.f, 0.f};
+      for (int i = 0; i < kTiles; ++i) o[i] = f32x4{0.f, 0.f, 0.f, 0.f};
     }
   };
 
   // A ring of kRing register buffers: kRing - 1 blocks are always in flight
   // while one is consumed, and no buffer is ever copied.
-  u32x4 kbuf[kRing][4], vbuf[kRing][4];
+  u32x4 kbuf[kRing][kKSteps];
+  VReg vbuf[kRing][kVLoads];
 #pragma unroll
   for (int i = 0; i < kRing - 1; ++i) issue(kbuf[i], vbuf[i], i);
   dB = describe(kWindow);
@@ -397,6 +442,8 @@ __global__ __launch_bounds__(kStreamWavesPerGroup * 64) void attn_stream_kernel(
     }
   }
   drain_records();
+  // Refused ids are reported once per wavefront, after the stream: nothing in the loop waits on it.
+  if (a.id_faults && refused && lane == 0) atomicAdd(a.id_faults, refused);
 }
 
 }  // namespace
@@ -406,14 +453,17 @@ hipError_t launch_attn_stream(const AttnLaunch& a_in, hipStream_t stream) {
   // LDS per workgroup: the prefix arrays, then as many parked records per
   // wavefront as fit in 64 KiB (at most 8).
   const size_t cum_bytes = (size_t)((2 * (a.S + 1) + 3) & ~3) * sizeof(int);
-  const size_t rec_bytes = (size_t)record_floats(a.G) * sizeof(float);
+  const size_t rec_bytes = (size_t)record_floats(a.G, a.D) * sizeof(float);
   const size_t room = (size_t)64 * 1024 - cum_bytes;
   a.rec_buffered = (int)(room / (kStreamWavesPerGroup * rec_bytes));
   if (a.rec_buffered > 8) a.rec_buffered = 8;
   if (a.rec_buffered < 1) return hipErrorInvalidValue;
   const size_t lds = cum_bytes + (size_t)kStreamWavesPerGroup * a.rec_buffered * rec_bytes;
-  hipLaunchKernelGGL(attn_stream_kernel, dim3(kStreamGroups), dim3(kStreamWavesPerGroup * 64), lds,
-                     stream, a);
+  const dim3 grid(a.waves / kStreamWavesPerGroup), block(kStreamWavesPerGroup * 64);
+  if (a.D == 64) hipLaunchKernelGGL(attn_stream_kernel<64>, grid, block, lds, stream, a);
+  else if (a.D == 128) hipLaunchKernelGGL(attn_stream_kernel<128>, grid, block, lds, stream, a);
+  else if (a.D == 256) hipLaunchKernelGGL(attn_stream_kernel<256>, grid, block, lds, stream, a);
+  else return hipErrorInvalidValue;
   return hipGetLastError();
 }
 

@@ -12,9 +12,9 @@ constexpr int kAppendThreads = 256;
 __global__ __launch_bounds__(kAppendThreads) void kv_append_kernel(
     const u32x4* __restrict__ k_new, const u32x4* __restrict__ v_new, u32x4* __restrict__ k_pool,
     u32x4* __restrict__ v_pool, const int32_t* __restrict__ block_tables,
-    const int32_t* __restrict__ context_lens, int S, int Hkv, int MAXB, int B, int max_ctx,
-    int NB) {
-  constexpr int kRowChunks = kHeadDim * 2 / 16;   // 16-byte chunks per row
+    const int32_t* __restrict__ context_lens, int S, int Hkv, int D, int MAXB, int B, int max_ctx,
+    int NB, int32_t* __restrict__ id_faults) {
+  const int kRowChunks = D * 2 / 16;   // 16-byte chunks per row
   const int64_t idx = (int64_t)blockIdx.x * kAppendThreads + threadIdx.x;   // (s, kvh, chunk)
   const int64_t total = (int64_t)S * Hkv * kRowChunks;
   if (idx >= total) return;
@@ -25,7 +25,10 @@ __global__ __launch_bounds__(kAppendThreads) void kv_append_kernel(
   if (L <= 0) return;
   const int t = L - 1;
   const int id = block_tables[(int64_t)s * MAXB + t / B];
-  if ((unsigned)id >= (unsigned)NB) return;   // never follow a corrupt id
+  if ((unsigned)id >= (unsigned)NB) {   // never follow a corrupt id; report it once per request
+    if (id_faults && kvh == 0 && chunk == 0) atomicAdd(id_faults, 1);
+    return;
+  }
   const int64_t dst = (((int64_t)id * Hkv + kvh) * B + t % B) * kRowChunks + chunk;
   k_pool[dst] = k_new[idx];
   v_pool[dst] = v_new[idx];
@@ -35,13 +38,13 @@ __global__ __launch_bounds__(kAppendThreads) void kv_append_kernel(
 
 hipError_t launch_kv_append(const uint16_t* k_new, const uint16_t* v_new, uint16_t* k_pool,
                             uint16_t* v_pool, const int32_t* block_tables,
-                            const int32_t* context_lens, int S, int Hkv, int MAXB, int B,
-                            int max_ctx, int NB, hipStream_t stream) {
-  const int64_t total = (int64_t)S * Hkv * (kHeadDim * 2 / 16);
+                            const int32_t* context_lens, int S, int Hkv, int D, int MAXB, int B,
+                            int max_ctx, int NB, int32_t* id_faults, hipStream_t stream) {
+  const int64_t total = (int64_t)S * Hkv * (D * 2 / 16);
   dim3 grid((unsigned)((total + kAppendThreads - 1) / kAppendThreads));
   hipLaunchKernelGGL(kv_append_kernel, grid, dim3(kAppendThreads), 0, stream, (const u32x4*)k_new,
                      (const u32x4*)v_new, (u32x4*)k_pool, (u32x4*)v_pool, block_tables,
-                     context_lens, S, Hkv, MAXB, B, max_ctx, NB);
+                     context_lens, S, Hkv, D, MAXB, B, max_ctx, NB, id_faults);
   return hipGetLastError();
 }
 

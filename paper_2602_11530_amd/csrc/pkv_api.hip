@@ -16,6 +16,7 @@ static __device__ __align__(256) unsigned char scratch[kStaticScratchBytes];
 namespace {
 
 thread_local hipError_t g_last_launch_error = hipSuccess;
+thread_local int32_t* g_id_faults = nullptr;   // see pkv_set_id_fault_counter
 
 inline bool misaligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) != 0; }
 
@@ -33,12 +34,15 @@ int check_shape(const pkv_attn_shape* sh, Geometry* g) {
   if (!sh) return PKV_ERR_NULL;
   if (sh->num_seqs < 0 || sh->num_seqs > pkv::kMaxSeqs) return PKV_ERR_SHAPE;
   if (sh->num_q_heads <= 0 || sh->num_kv_heads <= 0) return PKV_ERR_SHAPE;
-  if (sh->head_dim != pkv::kHeadDim) return PKV_ERR_SHAPE;
+  const int D = sh->head_dim;
+  if (D != 64 && D != 128 && D != 256) return PKV_ERR_SHAPE;
   const int B = sh->block_size;
   if (B != 16 && B != 32 && B != pkv::kMaxBlockSize) return PKV_ERR_SHAPE;
   if (sh->num_q_heads % sh->num_kv_heads != 0) return PKV_ERR_SHAPE;
   const int G = sh->num_q_heads / sh->num_kv_heads;
   if (G > pkv::kMaxGroup) return PKV_ERR_SHAPE;
+  // a wavefront parks a whole record (G rows of D floats) in its 16 KiB share of LDS
+  if (D == 256 && G > 8) return PKV_ERR_SHAPE;
   if (sh->max_blocks_per_seq <= 0) return PKV_ERR_SHAPE;
   if ((int64_t)sh->max_blocks_per_seq * B > INT32_MAX) return PKV_ERR_SHAPE;
   const int cap = sh->max_blocks_per_seq * B;
@@ -72,7 +76,7 @@ struct WorkspaceLayout {
 
 WorkspaceLayout workspace_layout(const pkv_attn_shape* sh, const Geometry& g) {
   WorkspaceLayout w;
-  w.rec_bytes = (size_t)g.slots * pkv::record_floats(g.G) * sizeof(float);
+  w.rec_bytes = (size_t)g.slots * pkv::record_floats(g.G, sh->head_dim) * sizeof(float);
   w.cum_bytes = ((size_t)(sh->num_seqs + 1) * sizeof(int32_t) + 15) & ~(size_t)15;
   return w;
 }
@@ -129,6 +133,12 @@ const char* pkv_status_string(int status) {
 
 const char* pkv_last_launch_error(void) { return hipGetErrorString(g_last_launch_error); }
 
+int pkv_set_id_fault_counter(int32_t* device_counter) {
+  if (reinterpret_cast<uintptr_t>(device_counter) & 3u) return PKV_ERR_ALIGN;
+  g_id_faults = device_counter;
+  return PKV_OK;
+}
+
 int pkv_attn_partition_size(const pkv_attn_shape* shape) {
   Geometry g;
   const int rc = check_shape(shape, &g);
@@ -168,6 +178,10 @@ static int prepare_attn(const int32_t* block_tables, const int32_t* context_lens
   a->Hq = shape->num_q_heads;
   a->Hkv = shape->num_kv_heads;
   a->G = g.G;
+  a->D = shape->head_dim;
+  // a D = 256 wavefront needs the registers of a whole SIMD lane: one wavefront per SIMD
+  a->waves = shape->head_dim == 256 ? pkv::kStreamWaves / 2 : pkv::kStreamWaves;
+  a->id_faults = g_id_faults;
   a->MAXB = shape->max_blocks_per_seq;
   a->upb = shape->block_size / pkv::kBlockTokens;
   a->P = g.P;
@@ -273,8 +287,9 @@ int kv_append(const void* k_new, const void* v_new, void* k_pool, void* v_pool,
   const hipError_t e = pkv::launch_kv_append(
       static_cast<const uint16_t*>(k_new), static_cast<const uint16_t*>(v_new),
       static_cast<uint16_t*>(k_pool), static_cast<uint16_t*>(v_pool), block_tables, context_lens,
-      shape->num_seqs, shape->num_kv_heads, shape->max_blocks_per_seq, shape->block_size, g.max_ctx,
-      (int)shape->num_pool_blocks, static_cast<hipStream_t>(stream));
+      shape->num_seqs, shape->num_kv_heads, shape->head_dim, shape->max_blocks_per_seq,
+      shape->block_size, g.max_ctx, (int)shape->num_pool_blocks, g_id_faults,
+      static_cast<hipStream_t>(stream));
   return launch_status(e);
 }
 
@@ -295,13 +310,18 @@ static int check_copy(const void* pool, const void* staging, const int32_t* bloc
 
 // The far end of an offload or reload must be page-locked host memory: only
 // then is the copy asynchronous and done by the DMA engines at link speed.
-static int check_pinned(const void* host) {
-  hipPointerAttribute_t attr;
-  if (hipPointerGetAttributes(&attr, host) != hipSuccess) {
-    (void)hipGetLastError();   // an unknown pointer is reported as an error; clear it
-    return PKV_ERR_HOST;
+static int check_pinned(const void* host, size_t bytes) {
+  // the first and the last byte must both lie in page-locked host memory
+  const char* ends[2] = {static_cast<const char*>(host), static_cast<const char*>(host) + (bytes - 1)};
+  for (const char* p : ends) {
+    hipPointerAttribute_t attr;
+    if (hipPointerGetAttributes(&attr, p) != hipSuccess) {
+      (void)hipGetLastError();   // an unknown pointer is reported as an error; clear it
+      return PKV_ERR_HOST;
+    }
+    if (attr.type != hipMemoryTypeHost) return PKV_ERR_HOST;
   }
-  return attr.type == hipMemoryTypeHost ? PKV_OK : PKV_ERR_HOST;
+  return PKV_OK;
 }
 
 static int copy_call(const void* pool, const void* staging, const int32_t* block_ids,
@@ -313,9 +333,9 @@ static int copy_call(const void* pool, const void* staging, const int32_t* block
   hipStream_t st = static_cast<hipStream_t>(stream);
   const hipError_t e =
       gather ? pkv::launch_kv_block_copy(pool, const_cast<void*>(staging), block_ids, n_blocks,
-                                         block_bytes, num_pool_blocks, true, st)
+                                         block_bytes, num_pool_blocks, true, g_id_faults, st)
              : pkv::launch_kv_block_copy(staging, const_cast<void*>(pool), block_ids, n_blocks,
-                                         block_bytes, num_pool_blocks, false, st);
+                                         block_bytes, num_pool_blocks, false, g_id_faults, st);
   return launch_status(e);
 }
 
@@ -341,7 +361,7 @@ int kv_blocks_move(const void* src_pool, const int32_t* src_ids, void* dst_pool,
       (reinterpret_cast<uintptr_t>(dst_ids) & 3u))
     return PKV_ERR_ALIGN;
   return launch_status(pkv::launch_kv_block_move(src_pool, src_ids, src_pool_blocks, dst_pool, dst_ids,
-                                                 dst_pool_blocks, n_blocks, block_bytes,
+                                                 dst_pool_blocks, n_blocks, block_bytes, g_id_faults,
                                                  static_cast<hipStream_t>(stream)));
 }
 
@@ -351,11 +371,11 @@ int kv_blocks_offload(const void* pool, const int32_t* block_ids, void* staging,
   int rc = check_copy(pool, staging, block_ids, n_blocks, block_bytes, num_pool_blocks, &empty);
   if (rc != PKV_OK || empty) return rc;
   if (!host_dst) return PKV_ERR_NULL;
-  rc = check_pinned(host_dst);
+  rc = check_pinned(host_dst, (size_t)n_blocks * (size_t)block_bytes);
   if (rc != PKV_OK) return rc;
   hipStream_t st = static_cast<hipStream_t>(stream);
   hipError_t e = pkv::launch_kv_block_copy(pool, staging, block_ids, n_blocks, block_bytes,
-                                           num_pool_blocks, true, st);
+                                           num_pool_blocks, true, g_id_faults, st);
   if (e != hipSuccess) return launch_status(e);
   e = hipMemcpyAsync(host_dst, staging, (size_t)n_blocks * (size_t)block_bytes,
                      hipMemcpyDeviceToHost, st);
@@ -368,14 +388,14 @@ int kv_blocks_reload(const void* host_src, void* staging, void* pool, const int3
   int rc = check_copy(pool, staging, block_ids, n_blocks, block_bytes, num_pool_blocks, &empty);
   if (rc != PKV_OK || empty) return rc;
   if (!host_src) return PKV_ERR_NULL;
-  rc = check_pinned(host_src);
+  rc = check_pinned(host_src, (size_t)n_blocks * (size_t)block_bytes);
   if (rc != PKV_OK) return rc;
   hipStream_t st = static_cast<hipStream_t>(stream);
   hipError_t e = hipMemcpyAsync(staging, host_src, (size_t)n_blocks * (size_t)block_bytes,
                                 hipMemcpyHostToDevice, st);
   if (e != hipSuccess) return launch_status(e);
   e = pkv::launch_kv_block_copy(staging, pool, block_ids, n_blocks, block_bytes, num_pool_blocks,
-                                false, st);
+                                false, g_id_faults, st);
   return launch_status(e);
 }
 

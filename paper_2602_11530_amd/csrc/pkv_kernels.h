@@ -9,7 +9,6 @@ namespace pkv {
 
 typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));  // one 16-byte lane load
 
-constexpr int kHeadDim = 128;        // D
 constexpr int kBlockTokens = 16;     // tokens per streaming unit (one MFMA tile of keys); a physical
                                      // block of B = 16, 32 or 64 tokens holds B/16 units per KV head
 constexpr int kMaxBlockSize = 64;
@@ -53,7 +52,7 @@ __host__ __device__ inline int share_owner(int64_t pos, int64_t T, int64_t W) {
 
 // One partial record: G un-normalised rows of D floats, then (reference max in
 // log2 units, partial sum) for up to kMaxGroup heads.  Rows are 16-byte multiples.
-__host__ __device__ inline int record_floats(int G) { return G * kHeadDim + 2 * kMaxGroup; }
+__host__ __device__ inline int record_floats(int G, int D) { return G * D + 2 * kMaxGroup; }
 
 struct AttnLaunch {
   const uint16_t* q;
@@ -65,7 +64,10 @@ struct AttnLaunch {
   float* ws_rec;   // [slots][record_floats(G)] partial records, see record_floats()
   int32_t* ws_cum; // [S + 1] cumB, written by the stream pass for the merge
   float scale_log2e;
+  int32_t* id_faults;  // optional device counter of refused block ids (nullptr: not reported)
   int S, Hq, Hkv, G, MAXB;
+  int D;           // head dimension: 64, 128 or 256
+  int waves;       // persistent wavefronts of the stream pass: kStreamWaves, or half of it for D = 256
   int upb;         // 16-token units per physical block (B / 16)
   int P;           // partition size, tokens
   int max_ctx;     // context lengths are clamped to [0, max_ctx] (<= MAXB * 16)
@@ -79,19 +81,22 @@ hipError_t launch_attn_stream(const AttnLaunch& a, hipStream_t stream);
 hipError_t launch_attn_reduce(const AttnLaunch& a, hipStream_t stream);
 
 // Whole-block copies; `gather` selects the direction.
+// `id_faults` (optional, device): incremented once per listed block that is skipped because an
+// id lies outside its pool.
 hipError_t launch_kv_block_copy(const void* src, void* dst, const int32_t* block_ids,
                                 int64_t n_blocks, int64_t block_bytes, int64_t num_pool_blocks,
-                                bool gather, hipStream_t stream);
+                                bool gather, int32_t* id_faults, hipStream_t stream);
 
 // Pool to pool: dst[dst_ids[i]] = src[src_ids[i]], no staging image in between.
 hipError_t launch_kv_block_move(const void* src, const int32_t* src_ids, int64_t src_pool_blocks,
                                 void* dst, const int32_t* dst_ids, int64_t dst_pool_blocks,
-                                int64_t n_blocks, int64_t block_bytes, hipStream_t stream);
+                                int64_t n_blocks, int64_t block_bytes, int32_t* id_faults,
+                                hipStream_t stream);
 
 // New token's K and V rows into slot context_lens[s] - 1 of every request.
 hipError_t launch_kv_append(const uint16_t* k_new, const uint16_t* v_new, uint16_t* k_pool,
                             uint16_t* v_pool, const int32_t* block_tables,
-                            const int32_t* context_lens, int S, int Hkv, int MAXB, int B,
-                            int max_ctx, int NB, hipStream_t stream);
+                            const int32_t* context_lens, int S, int Hkv, int D, int MAXB, int B,
+                            int max_ctx, int NB, int32_t* id_faults, hipStream_t stream);
 
 }  // namespace pkv

@@ -85,6 +85,7 @@ struct Server {
   int32_t *tables_d = nullptr, *lens_d = nullptr, *ids_d = nullptr, *ids2_d = nullptr;
   void* workspace = nullptr;
   size_t workspace_bytes = 0;
+  int32_t* id_faults = nullptr;   // device counter of block ids the kernels refused to follow
   int max_batch = 0;
   // pinned host
   uint16_t* h_stage = nullptr;                     // upload / download area, one request image
@@ -136,6 +137,11 @@ struct Server {
     pkv_attn_shape sh = shape(max_batch);
     PKV_OK_(pkv_attn_workspace_bytes(&sh, &workspace_bytes));
     HIP_OK(hipMalloc(&workspace, workspace_bytes));
+    // every order the scheduler issues must name blocks inside the pools: have the library count
+    // any id it refuses, and fail the run if the count is not zero at the end
+    HIP_OK(hipMalloc(&id_faults, sizeof(int32_t)));
+    HIP_OK(hipMemset(id_faults, 0, sizeof(int32_t)));
+    PKV_OK_(pkv_set_id_fault_counter(id_faults));
     HIP_OK(hipHostMalloc((void**)&h_stage, (size_t)maxb * kBlockBytes));
     HIP_OK(hipHostMalloc((void**)&h_tables, (size_t)max_batch * maxb * 4));
     HIP_OK(hipHostMalloc((void**)&h_lens, (size_t)max_batch * 4));
@@ -442,6 +448,13 @@ int main(int argc, char** argv) {
     int32_t free_blocks = 0;
     SCHED_OK(pascal_instance_signals(sv.sched, i, 1e18, nullptr, nullptr, nullptr, nullptr, &free_blocks));
     if (free_blocks != o.blocks || !sv.host_store.empty()) { std::fprintf(stderr, "blocks or images leaked\n"); return 9; }
+  }
+  {
+    int32_t refused = -1;
+    HIP_OK(hipDeviceSynchronize());
+    HIP_OK(hipMemcpy(&refused, sv.id_faults, sizeof refused, hipMemcpyDeviceToHost));
+    PKV_OK_(pkv_set_id_fault_counter(nullptr));
+    if (refused != 0) { std::fprintf(stderr, "the kernels refused %d block ids\n", refused); return 10; }
   }
   std::printf("{\"requests\": %d, \"instances\": %d, \"layers\": %d, \"iterations\": %ld, \"kv_checks\": %ld, "
               "\"offloads\": %ld, \"reloads\": %ld, \"migrations\": %ld, \"migrations_via_host\": %ld, "

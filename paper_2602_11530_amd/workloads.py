@@ -152,15 +152,16 @@ def make_tables(lens, num_pool_blocks: int, rng: np.random.Generator,
 def custom(lens, num_q_heads: int, num_kv_heads: int, seed: int,
            num_pool_blocks: Optional[int] = None, maxb: Optional[int] = None,
            partition_size: int = 0, name: str = "custom", fill: int = -1,
-           block_size: int = BLOCK_SIZE) -> Workload:
-    """Arbitrary lengths (edge-case sweeps), any block size."""
+           block_size: int = BLOCK_SIZE, head_dim: int = HEAD_DIM) -> Workload:
+    """Arbitrary lengths (edge-case sweeps), any block size and head dimension."""
     lens = np.asarray(lens, dtype=np.int32)
     need = int(((lens.astype(np.int64) + block_size - 1) // block_size).sum())
     nb = max(need, 1) if num_pool_blocks is None else num_pool_blocks
     rng = np.random.default_rng(seed)
     tables = make_tables(lens, nb, rng, block_size=block_size, maxb=maxb, fill=fill)
     return Workload(name, num_q_heads, num_kv_heads, lens, tables, nb,
-                    partition_size=partition_size, block_size=block_size, seed=seed)
+                    partition_size=partition_size, head_dim=head_dim, block_size=block_size,
+                    seed=seed)
 
 
 def cfg1_tiny(seed: int = BASE_SEED + 1) -> Workload:
@@ -172,14 +173,16 @@ def cfg1_tiny(seed: int = BASE_SEED + 1) -> Workload:
 
 
 def cfg2_qwen32b(seed: int = BASE_SEED + 2, batch: int = 64,
-                 lo: int = 1024, hi: int = 8192) -> Workload:
+                 lo: int = 1024, hi: int = 8192, head_dim: int = HEAD_DIM) -> Workload:
     """Batch 64, 40 query / 8 KV heads, lengths U{1024..8192}; the pool holds
-    exactly the batch and the tables are a shuffle of it."""
+    exactly the batch and the tables are a shuffle of it.  (``head_dim`` other
+    than 128 gives the same batch for the head-dimension variants.)"""
     rng = np.random.default_rng(seed)
     lens = rng.integers(lo, hi + 1, size=batch).astype(np.int32)
     nb = int(((lens.astype(np.int64) + BLOCK_SIZE - 1) // BLOCK_SIZE).sum())
     tables = make_tables(lens, nb, rng, maxb=(hi + BLOCK_SIZE - 1) // BLOCK_SIZE)
-    return Workload("cfg2_qwen32b_b64_u1024_8192", 40, 8, lens, tables, nb, seed=seed)
+    name = "cfg2_qwen32b_b64_u1024_8192" + ("" if head_dim == HEAD_DIM else f"_d{head_dim}")
+    return Workload(name, 40, 8, lens, tables, nb, head_dim=head_dim, seed=seed)
 
 
 def cfg3_long_cot(seed: int = BASE_SEED + 3, batch: int = 128) -> Workload:

@@ -47,6 +47,10 @@ def test_partition_and_workspace():
     sh.max_context_len = 512             # neither the bound nor the partition changes the size:
     sh.partition_size = 16               # runs are folded per (wavefront, segment) before they leave LDS
     assert pkv.pkv_attn_workspace_bytes(sh) == slots * rec + a16(129 * 4)
+    # head dimensions 64 and 256: the record rows follow D
+    for D, G in ((64, 5), (256, 5), (256, 8), (64, 16)):
+        shd = pkv.make_shape(128, 8 * G, 8, 2048, 70000, head_dim=D)
+        assert pkv.pkv_attn_workspace_bytes(shd) == slots * (G * D + 32) * 4 + a16(129 * 4)
     sh = pkv.make_shape(4, 8, 2, 19, 128)
     P = pkv.pkv_attn_partition_size(sh)
     assert P % 16 == 0 and 16 <= P <= 65536
@@ -54,7 +58,7 @@ def test_partition_and_workspace():
 
 
 @pytest.mark.parametrize("kw", [
-    dict(head_dim=64), dict(block_size=48), dict(block_size=128), dict(block_size=8),
+    dict(head_dim=96), dict(head_dim=32), dict(head_dim=512), dict(head_dim=256, num_q_heads=32), dict(block_size=48), dict(block_size=128), dict(block_size=8),
     dict(block_size=32, partition_size=16), dict(block_size=64, num_pool_blocks=2 ** 29), dict(num_q_heads=9), dict(num_kv_heads=0),
     dict(partition_size=24), dict(partition_size=65536 + 16), dict(num_seqs=2049), dict(partition_size=-16),
     dict(max_blocks_per_seq=0), dict(num_seqs=-1), dict(max_context_len=20 * 16),

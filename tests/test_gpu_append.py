@@ -14,7 +14,8 @@ from gpu_util import MAX_ABS, REL_L2, assert_launchable, run_attn_dev, shape_of,
 pytestmark = pytest.mark.gpu
 
 
-def test_append_bit_exact_and_skips(device):
+@pytest.mark.expects_id_faults
+def test_append_bit_exact_and_skips(device, id_faults):
     w = wl.custom([1, 16, 17, 0, 300, 33, 512, 513], 40, 8, seed=41, num_pool_blocks=120)
     assert_launchable(w)
     rng = np.random.default_rng(8)
@@ -28,7 +29,8 @@ def test_append_bit_exact_and_skips(device):
     wk, wv = oracle.kv_append(k_new, v_new, k, v, w.block_tables, w.context_lens)
     assert np.array_equal(to_bits(k_d).reshape(k.shape), wk)
     assert np.array_equal(to_bits(v_d).reshape(v.shape), wv)
-    # a table entry outside the pool is skipped, everything else still written
+    assert int(id_faults.item()) == 0
+    # a table entry outside the pool is skipped (and reported), everything else still written
     bad = w.block_tables.copy()
     bad[4, (300 - 1) // 16] = w.num_pool_blocks + 5
     bad[1, 0] = -3
@@ -36,6 +38,7 @@ def test_append_bit_exact_and_skips(device):
     pkv.kv_append(to_dev(k_new), to_dev(v_new), k_d, v_d, to_dev(bad), to_dev(w.context_lens),
                   shape_of(w))
     torch.cuda.synchronize()
+    assert int(id_faults.item()) == 2      # one report per skipped request
     lens_ok = w.context_lens.copy()
     lens_ok[[4, 1]] = 0
     wk, wv = oracle.kv_append(k_new, v_new, k, v, w.block_tables, lens_ok)

@@ -188,12 +188,15 @@ def test_cfg3_full_parity(device):
     check(w, q, k, v, got)
 
 
-def test_corrupt_table_entries_are_not_followed(device):
+@pytest.mark.expects_id_faults
+def test_corrupt_table_entries_are_not_followed(device, id_faults):
     """Ids outside the pool are never dereferenced: the tokens of such a block
-    drop out of the softmax, the other requests' rows are untouched."""
+    drop out of the softmax, the other requests' rows are untouched, and the
+    refused entries are reported through the fault counter."""
     w = wl.custom([300, 1000, 77, 40], 40, 8, seed=19, num_pool_blocks=200, partition_size=128)
     q, k, v = wl.make_host_tensors(w)
     good = run_attn(w, q, k, v).reshape(w.q_shape())
+    assert int(id_faults.item()) == 0
     bad = wl.Workload("bad", 40, 8, w.context_lens, w.block_tables.copy(), w.num_pool_blocks,
                       partition_size=128, seed=w.seed)
     bad.block_tables[0, 3] = -7
@@ -204,6 +207,8 @@ def test_corrupt_table_entries_are_not_followed(device):
     out = run_attn_dev(bad, *dev, check_tables=False)
     torch.cuda.synchronize()
     got = to_bits(out).reshape(w.q_shape())
+    # one report per refused 16-token unit and KV head: 1 + 2 + 3 table entries x 8 heads
+    assert int(id_faults.item()) == (1 + 2 + 3) * 8
     assert np.array_equal(got[2], good[2])
     assert not got[3].any()
     # requests 0 and 1 equal the checker's result with the unmapped tokens removed

@@ -179,6 +179,7 @@ def test_cfg5_migration_next_to_decode(device):
     together = [torch.full(ws_surv.q_shape(), 0x7FC1, dtype=torch.int16, device=device)
                 for _ in range(n_layers)]
     bb, NB = w.block_bytes, w.num_pool_blocks
+    torch.cuda.synchronize()   # the poison fills above ran on the default stream: finish them first
     for l, (q, k, v) in enumerate(layers):
         for pool in (k, v):
             pkv.kv_blocks_gather(pool, old_d, staging, n, bb, NB, stream_a)

@@ -89,9 +89,11 @@ def test_migration_keeps_attention_bitwise(device):
     assert np.array_equal(before, after)
 
 
-def test_out_of_range_ids_are_skipped(device):
+@pytest.mark.expects_id_faults
+def test_out_of_range_ids_are_skipped(device, id_faults):
     """The device never follows an id outside the pool: those list entries are
-    skipped and everything else is copied as usual."""
+    skipped, reported through the fault counter, and everything else is copied
+    as usual."""
     rng = np.random.default_rng(9)
     NB, bb = 12, 8 * 16 * 128 * 2
     pool = rng.integers(0, 65536, size=(NB, bb // 2)).astype(np.uint16)
@@ -103,16 +105,32 @@ def test_out_of_range_ids_are_skipped(device):
     torch.cuda.synchronize()
     got = to_bits(st).reshape(len(ids), -1)
     assert np.array_equal(got[ok], pool[ids[ok]]) and (got[~ok] == 0x5A5A).all()
+    assert int(id_faults.item()) == int((~ok).sum())
     dst = to_dev(np.zeros_like(pool))
     pkv.kv_blocks_scatter(st, dst, to_dev(ids), len(ids), bb, NB)
     torch.cuda.synchronize()
+    assert int(id_faults.item()) == 2 * int((~ok).sum())
+    # pool to pool: an entry is skipped, and counted once, when either of its ids is out of range
+    other = to_dev(np.zeros_like(pool))
+    good_ids = np.arange(len(ids), dtype=np.int32)
+    pkv.kv_blocks_move(pool_d, to_dev(ids), other, to_dev(good_ids), len(ids), bb, NB, NB)
+    pkv.kv_blocks_move(pool_d, to_dev(good_ids), other, to_dev(ids), len(ids), bb, NB, NB)
+    torch.cuda.synchronize()
+    assert int(id_faults.item()) == 4 * int((~ok).sum())
+    # switched off: nothing is counted, the entries are still skipped
+    pkv.pkv_set_id_fault_counter(None)
+    pkv.kv_blocks_gather(pool_d, to_dev(ids), st, len(ids), bb, NB)
+    torch.cuda.synchronize()
+    assert int(id_faults.item()) == 4 * int((~ok).sum())
+    pkv.pkv_set_id_fault_counter(id_faults)
     want = np.zeros_like(pool)
     want[ids[ok]] = pool[ids[ok]]
     assert np.array_equal(to_bits(dst), want)
 
 
+@pytest.mark.expects_id_faults
 @pytest.mark.parametrize("hkv,n", [(8, 37), (2, 5), (1, 1), (8, 700)])
-def test_move_bit_exact(device, hkv, n):
+def test_move_bit_exact(device, hkv, n, id_faults):
     """Pool to pool in one pass equals the oracle's move, and gather + scatter."""
     rng = np.random.default_rng(300 + n)
     NBs, NBd = max(2 * n, 8), max(3 * n, 5)
@@ -126,6 +144,7 @@ def test_move_bit_exact(device, hkv, n):
     torch.cuda.synchronize()
     assert np.array_equal(to_bits(dst_d), oracle.kv_blocks_move(src, a, dst, b))
     assert np.array_equal(to_bits(src_d), src), "the source pool must not change"
+    assert int(id_faults.item()) == 0
     # out-of-range entries on either side are skipped, the rest still moves
     a2, b2 = a.copy(), b.copy()
     a2[0] = NBs + 3
@@ -138,6 +157,7 @@ def test_move_bit_exact(device, hkv, n):
     keep[0] = False
     if n > 1:
         keep[-1] = False
+    assert int(id_faults.item()) == int((~keep).sum())
     assert np.array_equal(to_bits(dst_d), oracle.kv_blocks_move(src, a[keep], dst, b[keep]))
 
 

@@ -139,6 +139,7 @@ def test_two_instances_decode_concurrently(device):
     shapes = [shape_of(w) for w in ws_]
     wss = [torch.empty(pkv.pkv_attn_workspace_bytes(s), dtype=torch.uint8, device=device) for s in shapes]
     outs = [torch.full(w.q_shape(), 0x7FC1, dtype=torch.int16, device=device) for w in ws_]
+    torch.cuda.synchronize()   # the fills ran on the default stream; the side streams do not wait for it
     for rep in range(6):
         for i in (0, 1):
             q, k, v = dev[i]

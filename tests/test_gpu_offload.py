@@ -152,6 +152,7 @@ def test_offload_next_to_decode(device):
     shape_s = shape_of(ws_surv)
     ws_b = torch.empty(pkv.pkv_attn_workspace_bytes(shape_s), dtype=torch.uint8, device=device)
     out = torch.full(ws_surv.q_shape(), 0x7FC1, dtype=torch.int16, device=device)
+    torch.cuda.synchronize()   # the fill ran on the default stream; the side streams do not wait for it
 
     def decode(times):
         a, b = ev(), ev()
@@ -179,6 +180,7 @@ def test_offload_next_to_decode(device):
     # survivors never touch the victims' old or new blocks, so the reload may overlap too
     k_d[old_d.long()] = 0
     v_d[old_d.long()] = 0
+    torch.cuda.synchronize()   # default-stream writes before the reload on the side stream
     ms_in = timed_a(resume)
     assert torch.equal(k_d.index_select(0, new_d.long()).cpu(), want_k)
     assert torch.equal(v_d.index_select(0, new_d.long()).cpu(), want_v)

@@ -94,6 +94,29 @@ def test_brute_force_edge_lengths(lens):
             assert not ref[s].any()
 
 
+@pytest.mark.parametrize("D", [64, 256])
+@pytest.mark.parametrize("B", [16, 32])
+def test_brute_force_other_head_dims(D, B):
+    """The checker is generic in the head dimension; head dims 64 and 256 against the same dense
+    numpy brute force (and against torch's routine below), with the scale that goes with them."""
+    w = wl.custom([33, 1, 0, 257, 16, 700], 12, 4, seed=17 + D, num_pool_blocks=90, head_dim=D,
+                  block_size=B)
+    assert w.scale == np.float32(1.0 / math.sqrt(D))
+    q, k, v = wl.make_host_tensors(w, poison_unused=True)
+    assert q.shape[-1] == D and k.shape[-1] == D
+    ref = run(w, q, k, v)
+    assert np.isfinite(ref).all() and not ref[2].any()
+    assert np.abs(ref - brute_force(w, q, k, v, w.scale)).max() < 1e-12
+    qf = torch.from_numpy(wl.bf16_bits_to_f64(q).reshape(w.q_shape()))
+    for s in (0, 3, 5):
+        K = torch.from_numpy(depage(w, k, s)).repeat_interleave(3, dim=1)
+        V = torch.from_numpy(depage(w, v, s)).repeat_interleave(3, dim=1)
+        o = torch.nn.functional.scaled_dot_product_attention(
+            qf[s][:, None, :], K.permute(1, 0, 2), V.permute(1, 0, 2),
+            scale=float(np.float32(w.scale)))
+        assert np.abs(o[:, 0, :].numpy() - ref[s]).max() < 1e-12
+
+
 def test_library_attention_medium():
     """torch's fp64 scaled_dot_product_attention on de-paged, head-repeated rows."""
     w = wl.custom([700, 45, 1300], 40, 8, seed=23)
