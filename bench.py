@@ -52,6 +52,9 @@ def parse():
                     help="split-K partition in tokens (default: the workload's; 0 = library picks)")
     ap.add_argument("--migrate-fraction", type=float, default=0.25,
                     help="fraction of the requests whose blocks the step migrates (default 0.25)")
+    ap.add_argument("--kv-dtype", default="bf16", choices=["bf16", "fp8"],
+                    help="fp8: the same batch with one-byte E4M3 KV pools (cfg2/cfg3; a workload of its "
+                         "own, reported as such)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-cfg3", action="store_true", help="default run: skip the long-context sub-record")
     ap.add_argument("--no-migration", action="store_true",
@@ -168,6 +171,27 @@ def fill_layer(w, seed, dev):
     return q, pools[0], pools[1]
 
 
+KV_SCALES = (0.0134, 0.0171)   # E4M3 pools: 448 * scale covers 6 and 7.7 sigma of the N(0,1) rows
+
+
+def fill_layer_fp8(w, seed, dev):
+    """q in bf16; K and V pools as E4M3 bytes whose de-quantised values are ~N(0,1)."""
+    import torch
+    g = torch.Generator(device=dev)
+    g.manual_seed(seed)
+    q = torch.randn(w.q_shape(), generator=g, device=dev, dtype=torch.float32).to(torch.bfloat16)
+    pools = []
+    for scale in KV_SCALES:
+        p = torch.empty(w.pool_shape(), dtype=torch.uint8, device=dev)
+        flat = p.view(-1)
+        for o in range(0, flat.numel(), 1 << 28):
+            n = min(1 << 28, flat.numel() - o)
+            x = torch.randn(n, generator=g, device=dev, dtype=torch.float32) / scale
+            flat[o:o + n] = x.clamp_(-448.0, 448.0).to(torch.float8_e4m3fn).view(torch.uint8)
+        pools.append(p)
+    return q, pools[0], pools[1]
+
+
 def box_copy_bandwidth(dev):
     """Read+write GB/s of a plain device-to-device copy of 1 GiB on this machine (the practical
     ceiling for mixed traffic, reported next to the nominal peak)."""
@@ -206,7 +230,9 @@ def single_layer(args, w, dev, steps, warmup, cpu_baseline):
     from paper_2602_11530_amd import binding as pkv
     from paper_2602_11530_amd import workloads as wl
 
-    q, k_pool, v_pool = fill_layer(w, w.seed + 17, dev)
+    fp8 = args.kv_dtype == "fp8"
+    q, k_pool, v_pool = (fill_layer_fp8 if fp8 else fill_layer)(w, w.seed + 17, dev)
+    elem = 1 if fp8 else 2
     tables = torch.from_numpy(w.block_tables).to(dev)
     lens = torch.from_numpy(w.context_lens).to(dev)
     out = torch.empty(w.q_shape(), dtype=torch.bfloat16, device=dev)
@@ -222,18 +248,25 @@ def single_layer(args, w, dev, steps, warmup, cpu_baseline):
     n_mig = 0 if args.no_migration else len(mig.old_ids)
     old_ids = torch.from_numpy(mig.old_ids).to(dev)
     new_ids = torch.from_numpy(mig.new_ids).to(dev)
-    staging = torch.empty((max(n_mig, 1),) + tuple(w.pool_shape()[1:]), dtype=torch.bfloat16,
+    staging = torch.empty((max(n_mig, 1),) + tuple(w.pool_shape()[1:]), dtype=k_pool.dtype,
                           device=dev)
     scale = float(w.scale)
     stream = torch.cuda.current_stream()
-    bb, NB = w.block_bytes, w.num_pool_blocks
+    bb, NB = w.block_bytes * elem // 2, w.num_pool_blocks
+
+    def attention():
+        if fp8:
+            pkv.paged_decode_attn_fp8kv(q, k_pool, v_pool, tables, lens, scale, KV_SCALES[0],
+                                        KV_SCALES[1], out, shape, ws, stream)
+        else:
+            pkv.paged_decode_attn(q, k_pool, v_pool, tables, lens, scale, out, shape, ws, stream)
 
     # The migration permutes rows among the victims' blocks, so the attention
     # of later steps reads the same bytes in another order: same traffic.
     def step(ev=None):
         if ev is not None:
             ev[0].record(stream)
-        pkv.paged_decode_attn(q, k_pool, v_pool, tables, lens, scale, out, shape, ws, stream)
+        attention()
         if ev is not None:
             ev[1].record(stream)
         if n_mig:
@@ -258,7 +291,8 @@ def single_layer(args, w, dev, steps, warmup, cpu_baseline):
     ms_step = wall * 1e3 / steps
     attn_ms = np.array([e[0].elapsed_time(e[1]) for e in events])
     mig_ms = np.array([e[1].elapsed_time(e[2]) for e in events])
-    attn_bytes = w.attn_algorithmic_bytes()
+    # every valid K and V row once (at one or two bytes per element), q, out, tables, lengths
+    attn_bytes = w.attn_algorithmic_bytes() - (2 - elem) * w.total_tokens * w.num_kv_heads * w.head_dim * 2
     # each migrated block is read once and written once by the gather and again by the scatter
     mig_bytes = 2 * (2 * 2 * n_mig * bb + 2 * 4 * n_mig)
     step_bytes = attn_bytes + mig_bytes
@@ -267,7 +301,8 @@ def single_layer(args, w, dev, steps, warmup, cpu_baseline):
     res = {
         "ms_per_step": ms_step,
         "config": {
-            "workload": w.name,
+            "workload": w.name + ("_fp8kv" if fp8 else ""),
+            "kv_dtype": "e4m3 bytes, one fp32 scale per pool" if fp8 else "bf16",
             "num_seqs": w.num_seqs, "q_heads": w.num_q_heads, "kv_heads": w.num_kv_heads,
             "head_dim": w.head_dim, "block_size": w.block_size,
             "total_context_tokens": w.total_tokens, "pool_blocks": w.num_pool_blocks,
@@ -299,7 +334,7 @@ def single_layer(args, w, dev, steps, warmup, cpu_baseline):
             "kernel": "attn_stream_kernel (event-timed together with the small merge kernel that follows it)",
             "achieved": round(attn_gbps, 1), "peak": HBM_PEAK_GBPS, "unit": "GB/s",
             "frac": round(attn_gbps / HBM_PEAK_GBPS, 4),
-            "traffic": recorded_traffic(w.name, P),
+            "traffic": None if fp8 else recorded_traffic(w.name, P),
         },
         "cpu_baseline": None,
     }
@@ -307,9 +342,16 @@ def single_layer(args, w, dev, steps, warmup, cpu_baseline):
     if cpu_baseline:
         import oracle
         qh = q.view(torch.int16).cpu().numpy().view(np.uint16)
-        kh = k_pool.view(torch.int16).cpu().numpy().view(np.uint16)
-        vh = v_pool.view(torch.int16).cpu().numpy().view(np.uint16)
-        ref, secs, threads = oracle.timed_attn(qh, kh, vh, w.block_tables, w.context_lens, w.scale)
+        if fp8:
+            kh, vh = k_pool.cpu().numpy(), v_pool.cpu().numpy()
+            t0 = time.perf_counter()
+            ref = oracle.paged_decode_attn_fp8kv(qh, kh, vh, w.block_tables, w.context_lens, w.scale,
+                                                 KV_SCALES[0], KV_SCALES[1])
+            secs, threads = time.perf_counter() - t0, oracle.max_threads()
+        else:
+            kh = k_pool.view(torch.int16).cpu().numpy().view(np.uint16)
+            vh = v_pool.view(torch.int16).cpu().numpy().view(np.uint16)
+            ref, secs, threads = oracle.timed_attn(qh, kh, vh, w.block_tables, w.context_lens, w.scale)
         # The pools were copied after the timed loop; one more step attends over
         # exactly that state (its migration runs after its attention).
         step()
@@ -529,6 +571,8 @@ def main():
     # `value` is the metric's quantity: HBM GB/s of the attention call; the blended figure of the
     # whole step (attention + migration copies) is under "step"
     res = base_line(args, r["attn"]["GBps"], r["ms_per_step"], args.steps, args.warmup)
+    if args.kv_dtype == "fp8":
+        res["dtype"] = "bf16 arithmetic operands and output, e4m3 KV pools"
     res["pct_of_hbm_peak"] = r["attn"]["pct_of_hbm_peak"]
     res.update({k: v for k, v in r.items() if k != "ms_per_step"})
     copy_gbps = box_copy_bandwidth(dev)
@@ -539,7 +583,7 @@ def main():
     }
     ok = r.get("parity", {}).get("within_bar", True)
 
-    if args.workload == "cfg2" and not args.no_cfg3 and args.partition is None:
+    if args.workload == "cfg2" and not args.no_cfg3 and args.partition is None and args.kv_dtype == "bf16":
         # the long-context batch as specified (512-token partitions), in the same line
         w3 = wl.cfg3_long_cot()
         r3 = single_layer(args, w3, dev, max(10, min(args.steps, 50)), min(args.warmup, 5),

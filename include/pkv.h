@@ -140,6 +140,35 @@ int paged_decode_attn_layers(const void* const* q, const void* const* k_pools,
                              size_t workspace_bytes, void* stream);
 
 /*
+ * The same attention over KV pools stored in 8 bits: K and V are OCP FP8 E4M3
+ * bytes (1 sign, 4 exponent bits with bias 7, 3 mantissa bits; no infinities,
+ * 0x7F and 0xFF are NaN, largest finite value 448), one fp32 scale per pool:
+ *
+ *     K[.] = k_scale * e4m3(k_pool byte),     V[.] = v_scale * e4m3(v_pool byte),
+ *
+ * everything else as in paged_decode_attn (q and out bf16, fp32 arithmetic).
+ * The paper's decode step is bound by the bytes of the KV cache it reads
+ * (Section II-A); a one-byte cache halves them.  The paper fixes no quantised
+ * format: this one (per-pool scales, E4M3) is the library's choice.  The bytes
+ * are widened exactly (every E4M3 value is a bf16 value), k_scale joins the
+ * softmax scale and v_scale multiplies the normalised row, so the result is the
+ * attention of the de-quantised pools to the same tolerance as the bf16 call.
+ *
+ *   k_pool, v_pool  device  e4m3 [NB][Hkv][B][D], one byte per element: a block
+ *                   is Hkv * B * D bytes (16 KiB at 8 x 16 x 128); the copies
+ *                   (gather, scatter, move, offload, reload) take such a pool as
+ *                   it is, with that block_bytes
+ *   k_scale,v_scale positive finite fp32
+ *   shape           head_dim must be 128 (PKV_ERR_SHAPE otherwise)
+ * NaN bytes inside a request's valid rows propagate as NaN; unused slots and
+ * unused blocks may hold any bytes.
+ */
+int paged_decode_attn_fp8kv(const void* q, const void* k_pool, const void* v_pool,
+                            const int32_t* block_tables, const int32_t* context_lens, float scale,
+                            float k_scale, float v_scale, void* out, const pkv_attn_shape* shape,
+                            void* workspace, size_t workspace_bytes, void* stream);
+
+/*
  * paged_decode_attn for callers that cannot allocate device memory or carry a
  * workspace around: code under HIP graph capture, tight serving loops, harnesses
  * that forbid hipMalloc.  Same arguments, same kernels and bit-identical results,
@@ -263,6 +292,22 @@ int kv_blocks_reload(const void* host_src, void* staging, void* pool, const int3
 int kv_append(const void* k_new, const void* v_new, void* k_pool, void* v_pool,
               const int32_t* block_tables, const int32_t* context_lens,
               const pkv_attn_shape* shape, void* stream);
+
+/*
+ * kv_append for E4M3 pools (see paged_decode_attn_fp8kv): the new rows arrive in
+ * bf16 and are stored as
+ *     byte = e4m3( x / pool_scale )
+ * with the division in fp32, round to nearest even, and magnitudes beyond the
+ * format's largest value saturating to +-448 (E4M3 has no infinity).  Everything
+ * else as for kv_append.
+ *
+ *   k_new, v_new  device  bf16 [S][Hkv][D]
+ *   k_pool,v_pool device  e4m3 [NB][Hkv][B][D]
+ *   k_scale, v_scale  positive finite fp32; head_dim must be 128
+ */
+int kv_append_fp8(const void* k_new, const void* v_new, void* k_pool, void* v_pool,
+                  const int32_t* block_tables, const int32_t* context_lens, float k_scale,
+                  float v_scale, const pkv_attn_shape* shape, void* stream);
 
 /*
  * Optional report of block ids the kernels refused to follow.  No kernel of this

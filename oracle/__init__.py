@@ -42,6 +42,18 @@ def _load() -> ctypes.CDLL:
                                                      i64, i64, i64, i64, i64, i64, i64,
                                                      ctypes.c_int]
         lib.pkv_oracle_paged_decode_attn.restype = ctypes.c_int
+        lib.pkv_oracle_paged_decode_attn_fp8kv.argtypes = [p, p, p, p, p, ctypes.c_float,
+                                                           ctypes.c_float, ctypes.c_float, p,
+                                                           i64, i64, i64, i64, i64, i64, i64,
+                                                           ctypes.c_int]
+        lib.pkv_oracle_paged_decode_attn_fp8kv.restype = ctypes.c_int
+        lib.pkv_oracle_to_e4m3.argtypes = [ctypes.c_float]
+        lib.pkv_oracle_to_e4m3.restype = ctypes.c_uint8
+        lib.pkv_oracle_kv_append_fp8.argtypes = [p, p, p, p, p, p, ctypes.c_float, ctypes.c_float,
+                                                 i64, i64, i64, i64, i64, i64]
+        lib.pkv_oracle_kv_append_fp8.restype = ctypes.c_int
+        lib.pkv_oracle_e4m3.argtypes = [ctypes.c_uint8]
+        lib.pkv_oracle_e4m3.restype = ctypes.c_double
         lib.pkv_oracle_kv_blocks_gather.argtypes = [p, p, p, i64, i64, i64]
         lib.pkv_oracle_kv_blocks_gather.restype = ctypes.c_int
         lib.pkv_oracle_kv_blocks_scatter.argtypes = [p, p, p, i64, i64, i64]
@@ -87,6 +99,60 @@ def paged_decode_attn(q, k_pool, v_pool, block_tables, context_lens, scale,
     rc = _load().pkv_oracle_paged_decode_attn(
         q.ctypes.data, k_pool.ctypes.data, v_pool.ctypes.data, block_tables.ctypes.data,
         context_lens.ctypes.data, ctypes.c_float(np.float32(scale)), ref.ctypes.data,
+        S, Hq, Hkv, D, B, block_tables.shape[1], NB, int(threads))
+    if rc != 0:
+        raise ValueError(f"oracle rejected its input (code {rc})")
+    return ref
+
+
+def e4m3(byte: int) -> float:
+    """Value of one OCP FP8 E4M3 byte (NaN for 0x7F and 0xFF)."""
+    return float(_load().pkv_oracle_e4m3(int(byte) & 0xFF))
+
+
+def to_e4m3(y) -> int:
+    """E4M3 byte of one fp32 value: nearest, ties to even, saturating at +-448."""
+    return int(_load().pkv_oracle_to_e4m3(ctypes.c_float(np.float32(y))))
+
+
+def kv_append_fp8(k_new, v_new, k_pool, v_pool, block_tables, context_lens, k_scale, v_scale):
+    """Copies of the E4M3 pools with every request's newest K,V row (bf16 bits [S,Hkv,D]), divided
+    by the pool's scale and rounded to E4M3, at position L_s - 1."""
+    k_new, v_new = _c(k_new, np.uint16), _c(v_new, np.uint16)
+    k_out = np.array(_c(k_pool, np.uint8), copy=True, order="C")
+    v_out = np.array(_c(v_pool, np.uint8), copy=True, order="C")
+    block_tables, context_lens = _c(block_tables, np.int32), _c(context_lens, np.int32)
+    S, Hkv, D = k_new.shape
+    NB, Hkv2, B, D2 = k_out.shape
+    if (Hkv2, D2) != (Hkv, D) or v_new.shape != k_new.shape or v_out.shape != k_out.shape:
+        raise ValueError("inconsistent shapes")
+    rc = _load().pkv_oracle_kv_append_fp8(k_new.ctypes.data, v_new.ctypes.data, k_out.ctypes.data,
+                                          v_out.ctypes.data, block_tables.ctypes.data,
+                                          context_lens.ctypes.data, ctypes.c_float(np.float32(k_scale)),
+                                          ctypes.c_float(np.float32(v_scale)), S, Hkv, D, B,
+                                          block_tables.shape[1], NB)
+    if rc != 0:
+        raise ValueError(f"oracle rejected its input (code {rc})")
+    return k_out, v_out
+
+
+def paged_decode_attn_fp8kv(q, k_pool, v_pool, block_tables, context_lens, scale, k_scale, v_scale,
+                            threads: int = 0) -> np.ndarray:
+    """fp64 reference [S, Hq, D] for E4M3 pools: q bf16 bits [S,Hq,D]; k_pool, v_pool uint8
+    [NB,Hkv,B,D]; K = k_scale * e4m3(byte), V = v_scale * e4m3(byte) (scales cast to fp32)."""
+    q = _c(q, np.uint16)
+    k_pool, v_pool = _c(k_pool, np.uint8), _c(v_pool, np.uint8)
+    block_tables, context_lens = _c(block_tables, np.int32), _c(context_lens, np.int32)
+    S, Hq, D = q.shape
+    NB, Hkv, B, D2 = k_pool.shape
+    if v_pool.shape != k_pool.shape or D2 != D or block_tables.shape[0] != S \
+            or context_lens.shape != (S,):
+        raise ValueError("inconsistent shapes")
+    ref = np.empty((S, Hq, D), dtype=np.float64)
+    rc = _load().pkv_oracle_paged_decode_attn_fp8kv(
+        q.ctypes.data, k_pool.ctypes.data, v_pool.ctypes.data, block_tables.ctypes.data,
+        context_lens.ctypes.data, ctypes.c_float(np.float32(scale)),
+        ctypes.c_float(np.float32(k_scale)), ctypes.c_float(np.float32(v_scale)), ref.ctypes.data,
         S, Hq, Hkv, D, B, block_tables.shape[1], NB, int(threads))
     if rc != 0:
         raise ValueError(f"oracle rejected its input (code {rc})")

@@ -35,6 +35,15 @@
  *
  * Pool layout: [NB, Hkv, B, D] row-major for K and for V.
  *
+ *   8-bit pools (a reading: the paper fixes no quantised cache format).  K and V
+ *   bytes are OCP FP8 E4M3: sign, 4 exponent bits (bias 7), 3 mantissa bits;
+ *   exponent field 0 is subnormal (m * 2^-9), there are no infinities, 0x7F and
+ *   0xFF are NaN.  One fp32 scale per pool: K = k_scale * e4m3(byte),
+ *   V = v_scale * e4m3(byte); the attention above is then taken over those
+ *   values.  Pinned against a library decode of all 256 bytes, a dense brute
+ *   force over de-quantised rows, and the bf16 function on a pool holding the
+ *   same values.
+ *
  * Parity pins (tests, CPU only): dense brute force written in numpy on tiny
  * inputs, a library fp64 attention on de-paged tensors, closed forms (L = 1,
  * scale = 0, V == 1, a two-token ln 2 case), shift, paging and GQA
@@ -55,6 +64,43 @@ static double widen_bf16(uint16_t bits) {
   return (double)f;
 }
 
+/* One OCP FP8 E4M3 byte, exactly. */
+double pkv_oracle_e4m3(uint8_t b) {
+  const int e = (b >> 3) & 15, m = b & 7;
+  double v;
+  if (e == 15 && m == 7) return NAN;
+  if (e == 0) v = ldexp((double)m, -9);
+  else v = ldexp(1.0 + m / 8.0, e - 7);
+  return (b & 0x80) ? -v : v;
+}
+
+/* fp32 -> E4M3 byte: round to nearest, ties to even, magnitudes above 448 saturate to 448
+ * (there is no infinity to overflow to); NaN gives the NaN byte with the input's sign.
+ * Written from the format: below 2^-6 the grid is m * 2^-9, m = 0..7; from there on
+ * (1 + m/8) * 2^(e-7), e = 1..15, with (e, m) = (15, 7) left out. */
+uint8_t pkv_oracle_to_e4m3(float y) {
+  const uint8_t sign = signbit(y) ? 0x80 : 0x00;
+  if (isnan(y)) return (uint8_t)(sign | 0x7F);
+  double a = fabs((double)y);
+  if (a > 448.0) a = 448.0;
+  if (a < ldexp(1.0, -6)) {
+    const int m = (int)nearbyint(ldexp(a, 9));        /* 0..8, ties to even */
+    return (uint8_t)(sign | m);                       /* m == 8 is the byte of 2^-6 */
+  }
+  int ex;
+  const double f = frexp(a, &ex);                     /* a = f * 2^ex, f in [0.5, 1) */
+  int e = ex - 1;                                     /* a = (2f) * 2^e, 2f in [1, 2) */
+  int m = (int)nearbyint((2.0 * f - 1.0) * 8.0);      /* 0..8, ties to even */
+  if (m == 8) { m = 0; e += 1; }
+  return (uint8_t)(sign | ((e + 7) << 3) | m);
+}
+
+/* Element idx of a K or V pool: a bf16 bit pattern, or an E4M3 byte times the pool's scale. */
+static double kv_value(const void* pool, int64_t idx, int fp8, double pool_scale) {
+  if (fp8) return pool_scale * pkv_oracle_e4m3(((const uint8_t*)pool)[idx]);
+  return widen_bf16(((const uint16_t*)pool)[idx]);
+}
+
 int pkv_oracle_max_threads(void) {
 #ifdef _OPENMP
   return omp_get_max_threads();
@@ -65,11 +111,11 @@ int pkv_oracle_max_threads(void) {
 
 /* Returns 0, or -1 on a bad argument, -2 if a dereferenced table entry is
  * outside [0, NB), -3 on allocation failure.  threads <= 0 means "all". */
-int pkv_oracle_paged_decode_attn(const uint16_t* q, const uint16_t* k_pool,
-                                 const uint16_t* v_pool, const int32_t* block_tables,
-                                 const int32_t* context_lens, float scale, double* ref,
-                                 int64_t S, int64_t Hq, int64_t Hkv, int64_t D, int64_t B,
-                                 int64_t MAXB, int64_t NB, int threads) {
+static int attn_definition(const uint16_t* q, const void* k_pool, const void* v_pool, int fp8,
+                           double k_scale, double v_scale, const int32_t* block_tables,
+                           const int32_t* context_lens, float scale, double* ref,
+                           int64_t S, int64_t Hq, int64_t Hkv, int64_t D, int64_t B,
+                           int64_t MAXB, int64_t NB, int threads) {
   if (S < 0 || Hq <= 0 || Hkv <= 0 || D <= 0 || B <= 0 || MAXB <= 0 || Hq % Hkv) return -1;
   const int64_t G = Hq / Hkv;
   for (int64_t s = 0; s < S; ++s) {
@@ -98,9 +144,9 @@ int pkv_oracle_paged_decode_attn(const uint16_t* q, const uint16_t* k_pool,
       /* scores */
       for (int64_t t = 0; t < L; ++t) {
         const int64_t pb = block_tables[s * MAXB + t / B];
-        const uint16_t* krow = k_pool + ((pb * Hkv + kvh) * B + t % B) * D;
+        const int64_t krow = ((pb * Hkv + kvh) * B + t % B) * D;
         double dot = 0.0;
-        for (int64_t d = 0; d < D; ++d) dot += widen_bf16(qrow[d]) * widen_bf16(krow[d]);
+        for (int64_t d = 0; d < D; ++d) dot += widen_bf16(qrow[d]) * kv_value(k_pool, krow + d, fp8, k_scale);
         x[t] = (double)scale * dot;
       }
       /* softmax weights */
@@ -111,14 +157,61 @@ int pkv_oracle_paged_decode_attn(const uint16_t* q, const uint16_t* k_pool,
       /* weighted sum of V rows */
       for (int64_t t = 0; t < L; ++t) {
         const int64_t pb = block_tables[s * MAXB + t / B];
-        const uint16_t* vrow = v_pool + ((pb * Hkv + kvh) * B + t % B) * D;
+        const int64_t vrow = ((pb * Hkv + kvh) * B + t % B) * D;
         const double w = x[t] / Z;
-        for (int64_t e = 0; e < D; ++e) o[e] += w * widen_bf16(vrow[e]);
+        for (int64_t e = 0; e < D; ++e) o[e] += w * kv_value(v_pool, vrow + e, fp8, v_scale);
       }
       free(x);
     }
   }
   return fail ? -3 : 0;
+}
+
+int pkv_oracle_paged_decode_attn(const uint16_t* q, const uint16_t* k_pool,
+                                 const uint16_t* v_pool, const int32_t* block_tables,
+                                 const int32_t* context_lens, float scale, double* ref,
+                                 int64_t S, int64_t Hq, int64_t Hkv, int64_t D, int64_t B,
+                                 int64_t MAXB, int64_t NB, int threads) {
+  return attn_definition(q, k_pool, v_pool, 0, 1.0, 1.0, block_tables, context_lens, scale, ref,
+                         S, Hq, Hkv, D, B, MAXB, NB, threads);
+}
+
+/* The same definition over E4M3 pools; k_scale and v_scale are the fp32 values the library is
+ * given, widened. */
+int pkv_oracle_paged_decode_attn_fp8kv(const uint16_t* q, const uint8_t* k_pool,
+                                       const uint8_t* v_pool, const int32_t* block_tables,
+                                       const int32_t* context_lens, float scale, float k_scale,
+                                       float v_scale, double* ref, int64_t S, int64_t Hq,
+                                       int64_t Hkv, int64_t D, int64_t B, int64_t MAXB, int64_t NB,
+                                       int threads) {
+  return attn_definition(q, k_pool, v_pool, 1, (double)k_scale, (double)v_scale, block_tables,
+                         context_lens, scale, ref, S, Hq, Hkv, D, B, MAXB, NB, threads);
+}
+
+/* The append step for E4M3 pools: the new rows are divided by their pool's scale in fp32 (the
+ * precision the device takes that decision in) and rounded to E4M3 as above. */
+int pkv_oracle_kv_append_fp8(const uint16_t* k_new, const uint16_t* v_new, uint8_t* k_pool,
+                             uint8_t* v_pool, const int32_t* block_tables,
+                             const int32_t* context_lens, float k_scale, float v_scale, int64_t S,
+                             int64_t Hkv, int64_t D, int64_t B, int64_t MAXB, int64_t NB) {
+  for (int64_t s = 0; s < S; ++s) {
+    const int64_t L = context_lens[s];
+    if (L <= 0) continue;
+    const int64_t t = L - 1;
+    if (t / B >= MAXB) return -1;
+    const int64_t pb = block_tables[s * MAXB + t / B];
+    if (pb < 0 || pb >= NB) return -2;
+    for (int64_t h = 0; h < Hkv; ++h) {
+      const int64_t dst = ((pb * Hkv + h) * B + t % B) * D;
+      for (int64_t d = 0; d < D; ++d) {
+        const float kx = (float)widen_bf16(k_new[(s * Hkv + h) * D + d]);
+        const float vx = (float)widen_bf16(v_new[(s * Hkv + h) * D + d]);
+        k_pool[dst + d] = pkv_oracle_to_e4m3(kx / k_scale);
+        v_pool[dst + d] = pkv_oracle_to_e4m3(vx / v_scale);
+      }
+    }
+  }
+  return 0;
 }
 
 /* staging[i] = pool[ids[i]], whole pages of block_bytes bytes. */

@@ -24,9 +24,9 @@ PKV_ERR_HOST = -6
 
 EXPORTS = (
     "pkv_attn_partition_size", "pkv_attn_workspace_bytes", "paged_decode_attn",
-    "paged_decode_attn_layers", "paged_decode_attn_static",
+    "paged_decode_attn_layers", "paged_decode_attn_static", "paged_decode_attn_fp8kv",
     "kv_blocks_gather", "kv_blocks_scatter", "kv_blocks_move", "kv_blocks_offload", "kv_blocks_reload",
-    "kv_append", "pkv_set_id_fault_counter", "pkv_status_string",
+    "kv_append", "kv_append_fp8", "pkv_set_id_fault_counter", "pkv_status_string",
     "pkv_last_launch_error", "pkv_version",
 )
 
@@ -81,6 +81,9 @@ def lib() -> ctypes.CDLL:
         L.paged_decode_attn.argtypes = [vp, vp, vp, i32p, i32p, ctypes.c_float, vp, shp, vp,
                                         ctypes.c_size_t, vp]
         L.paged_decode_attn.restype = ctypes.c_int
+        L.paged_decode_attn_fp8kv.argtypes = [vp, vp, vp, i32p, i32p, ctypes.c_float, ctypes.c_float,
+                                              ctypes.c_float, vp, shp, vp, ctypes.c_size_t, vp]
+        L.paged_decode_attn_fp8kv.restype = ctypes.c_int
         L.paged_decode_attn_static.argtypes = [vp, vp, vp, i32p, i32p, ctypes.c_float, vp, shp, vp]
         L.paged_decode_attn_static.restype = ctypes.c_int
         L.paged_decode_attn_layers.argtypes = [vp, vp, vp, i32p, i32p, ctypes.c_float, vp,
@@ -98,6 +101,8 @@ def lib() -> ctypes.CDLL:
         L.kv_blocks_reload.restype = ctypes.c_int
         L.pkv_set_id_fault_counter.argtypes = [vp]
         L.pkv_set_id_fault_counter.restype = ctypes.c_int
+        L.kv_append_fp8.argtypes = [vp, vp, vp, vp, i32p, i32p, ctypes.c_float, ctypes.c_float, shp, vp]
+        L.kv_append_fp8.restype = ctypes.c_int
         L.kv_append.argtypes = [vp, vp, vp, vp, i32p, i32p, shp, vp]
         L.kv_append.restype = ctypes.c_int
         _lib = L
@@ -162,6 +167,17 @@ def paged_decode_attn(q, k_pool, v_pool, block_tables, context_lens, scale, out,
                                    _ptr(context_lens), ctypes.c_float(scale), _ptr(out),
                                    ctypes.byref(shape), _ptr(workspace), ws_bytes,
                                    _stream(stream)))
+
+
+def paged_decode_attn_fp8kv(q, k_pool, v_pool, block_tables, context_lens, scale, k_scale, v_scale,
+                            out, shape: AttnShape, workspace=None, stream=None) -> None:
+    """Attention over e4m3 KV pools (one byte per element, one fp32 scale per pool)."""
+    ws_bytes = 0 if workspace is None else workspace.numel() * workspace.element_size()
+    _check(lib().paged_decode_attn_fp8kv(_ptr(q), _ptr(k_pool), _ptr(v_pool), _ptr(block_tables),
+                                         _ptr(context_lens), ctypes.c_float(scale),
+                                         ctypes.c_float(k_scale), ctypes.c_float(v_scale), _ptr(out),
+                                         ctypes.byref(shape), _ptr(workspace), ws_bytes,
+                                         _stream(stream)))
 
 
 STATIC_WORKSPACE_BYTES = 32 << 20
@@ -236,3 +252,11 @@ def kv_append(k_new, v_new, k_pool, v_pool, block_tables, context_lens, shape: A
     _check(lib().kv_append(_ptr(k_new), _ptr(v_new), _ptr(k_pool), _ptr(v_pool),
                            _ptr(block_tables), _ptr(context_lens), ctypes.byref(shape),
                            _stream(stream)))
+
+
+def kv_append_fp8(k_new, v_new, k_pool, v_pool, block_tables, context_lens, k_scale, v_scale,
+                  shape: AttnShape, stream=None) -> None:
+    """Quantise each request's newest K and V rows to E4M3 and write them into slot context_lens[s] - 1."""
+    _check(lib().kv_append_fp8(_ptr(k_new), _ptr(v_new), _ptr(k_pool), _ptr(v_pool),
+                               _ptr(block_tables), _ptr(context_lens), ctypes.c_float(k_scale),
+                               ctypes.c_float(v_scale), ctypes.byref(shape), _stream(stream)))

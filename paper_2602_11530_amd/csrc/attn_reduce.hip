@@ -111,7 +111,7 @@ __global__ __launch_bounds__(kRowsPerGroup * 64) void attn_reduce_kernel(AttnLau
     }
   }
   lsum = wave_sum(lsum);
-  const float inv = lsum > 0.f ? 1.f / lsum : 0.f;
+  const float inv = lsum > 0.f ? a.out_scale / lsum : 0.f;
   uint16_t r[kPer];
 #pragma unroll
   for (int i = 0; i < kPer; ++i) r[i] = bf16_bits(acc[i] * inv);

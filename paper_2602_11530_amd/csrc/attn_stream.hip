@@ -59,18 +59,25 @@ constexpr int kWindow = 64;       // descriptors per window: one per lane
 
 // What depends on the head dimension.  kRing: 16-token blocks in flight per
 // wavefront plus the one being consumed (a ring of register buffers).
-template <int kD> struct Dim;
-template <> struct Dim<64> {
-  static constexpr int kKSteps = 2, kVLoads = 4, kTiles = 4, kRing = 8;
+template <int kD, bool kFp8> struct Dim;
+template <> struct Dim<64, false> {
+  static constexpr int kKSteps = 2, kKLoads = 2, kVLoads = 4, kTiles = 4, kRing = 8, kElemBytes = 2;
   typedef uint32_t VReg __attribute__((ext_vector_type(2)));
 };
-template <> struct Dim<128> {
-  static constexpr int kKSteps = 4, kVLoads = 4, kTiles = 8, kRing = 4;
+template <> struct Dim<128, false> {
+  static constexpr int kKSteps = 4, kKLoads = 4, kVLoads = 4, kTiles = 8, kRing = 4, kElemBytes = 2;
   typedef uint32_t VReg __attribute__((ext_vector_type(4)));
 };
-template <> struct Dim<256> {
-  static constexpr int kKSteps = 8, kVLoads = 8, kTiles = 16, kRing = 4;
+template <> struct Dim<256, false> {
+  static constexpr int kKSteps = 8, kKLoads = 8, kVLoads = 8, kTiles = 16, kRing = 4, kElemBytes = 2;
   typedef uint32_t VReg __attribute__((ext_vector_type(4)));
+};
+// K and V stored as one-byte e4m3 values (D = 128): a block is half the bytes, so the ring is
+// twice as deep; the values are widened to bf16 (exactly) in registers and then take the same
+// path as a bf16 pool.
+template <> struct Dim<128, true> {
+  static constexpr int kKSteps = 4, kKLoads = 2, kVLoads = 4, kTiles = 8, kRing = 8, kElemBytes = 1;
+  typedef uint32_t VReg __attribute__((ext_vector_type(2)));
 };
 // First dim of output tiles 4t..4t+3 (they are consecutive dims) in the lane of column n.
 template <int kD> __device__ __forceinline__ int tile_group_dim(int t, int n) {
@@ -99,6 +106,13 @@ __device__ __forceinline__ float bf16_round(float x, uint32_t& bits) {
   return __uint_as_float(bits << 16);
 }
 
+// Four e4m3 bytes of one dword -> four bf16 (exact: every e4m3 value is a bf16 value).
+__device__ __forceinline__ u32x2 widen_e4m3x4(uint32_t w) {
+  const f32x2 lo = __builtin_amdgcn_cvt_pk_f32_fp8((int)w, false);
+  const f32x2 hi = __builtin_amdgcn_cvt_pk_f32_fp8((int)w, true);
+  return u32x2{pack_bf16(lo.x, lo.y), pack_bf16(hi.x, hi.y)};
+}
+
 // Stores of a finished run's record.  They are written as opaque instructions on
 // purpose: gfx9-family hardware counts loads and stores in one counter, and once
 // the compiler knows a store is pending it can no longer wait for "all but the N
@@ -124,11 +138,13 @@ struct Window {
 constexpr int kMetaLast = 1 << 8;
 constexpr int kMetaSegFirst = 1 << 9;
 
-template <int kD>
+template <int kD, bool kFp8>
 __global__ __launch_bounds__(kStreamWavesPerGroup * 64) void attn_stream_kernel(AttnLaunch a) {
-  typedef Dim<kD> DD;
-  typedef typename DD::VReg VReg;
-  constexpr int kKSteps = DD::kKSteps, kVLoads = DD::kVLoads, kTiles = DD::kTiles, kRing = DD::kRing;
+  typedef Dim<kD, kFp8> DD;
+  typedef typename DD::VReg VReg;                 // one V load as it arrives
+  typedef typename Dim<kD, false>::VReg VOp;      // the same rows as bf16
+  constexpr int kKSteps = DD::kKSteps, kKLoads = DD::kKLoads, kVLoads = DD::kVLoads,
+                kTiles = DD::kTiles, kRing = DD::kRing, kElemBytes = DD::kElemBytes;
   static_assert(kWindow % kRing == 0, "the window must be a whole number of ring turns");
   extern __shared__ int smem[];
   int* cumB = smem;                  // [S+1] blocks before request s
@@ -215,9 +231,9 @@ __global__ __launch_bounds__(kStreamWavesPerGroup * 64) void attn_stream_kernel(
   Window dB = dA;   // described after the first KV loads are on their way (below)
   int jbase = 0;
 
-  const int64_t head_elems = (int64_t)kBlockTokens * kD;  // one (block, KV head) slab
+  const int64_t slab_bytes = (int64_t)kBlockTokens * kD * kElemBytes;  // one (block, KV head) slab
   const int tau = 4 * (n & 3) + (n >> 2);
-  const int koff = tau * (kD / 8) + c;   // in 16-byte units within the slab
+  const int koff = tau * (kD * kElemBytes / 16) + c;   // in 16-byte units within the slab
   // V, in units of one VReg: token 4*e + c, this lane's dims (of half h when D = 256)
   const int voff = kD == 256 ? 32 * c + n : lane;
 
@@ -233,17 +249,17 @@ __global__ __launch_bounds__(kStreamWavesPerGroup * 64) void attn_stream_kernel(
   // caches it passes through.  The loads are unconditional so that every wait in the loop knows
   // exactly how many are outstanding: a block that is unmapped, or an index past
   // the share's end, reads slab 0 (which always exists) and is masked or skipped.
-  auto issue = [&](u32x4 (&k)[kKSteps], VReg (&v)[kVLoads], int j) {
+  auto issue = [&](u32x4 (&k)[kKLoads], VReg (&v)[kVLoads], int j) {
     const int idx = j - jbase;   // 0 .. 2*kWindow-1
     const int sa = __builtin_amdgcn_readlane(dA.slab, idx & (kWindow - 1));
     const int sb = __builtin_amdgcn_readlane(dB.slab, idx & (kWindow - 1));
     int slab = (idx < kWindow) ? sa : sb;
     if (j >= nshare) slab = 0;
-    const int64_t base = (int64_t)slab * head_elems;
-    const u32x4* kp = (const u32x4*)(a.k_pool + base) + koff;
-    const VReg* vp = (const VReg*)(a.v_pool + base) + voff;
+    const int64_t base = (int64_t)slab * slab_bytes;
+    const u32x4* kp = (const u32x4*)((const char*)a.k_pool + base) + koff;
+    const VReg* vp = (const VReg*)((const char*)a.v_pool + base) + voff;
 #pragma unroll
-    for (int jj = 0; jj < kKSteps; ++jj) k[jj] = __builtin_nontemporal_load(kp + 4 * jj);
+    for (int jj = 0; jj < kKLoads; ++jj) k[jj] = __builtin_nontemporal_load(kp + 4 * jj);
     if (kD == 256) {
 #pragma unroll
       for (int e = 0; e < 4; ++e) {
@@ -275,8 +291,32 @@ __global__ __launch_bounds__(kStreamWavesPerGroup * 64) void attn_stream_kernel(
     nrec = 0;
   };
 
-  auto consume = [&](u32x4 (&k)[kKSteps], VReg (&v)[kVLoads], int j) {
+  auto consume = [&](u32x4 (&kraw)[kKLoads], VReg (&vraw)[kVLoads], int j) {
     const int idx = j - jbase;   // always inside window A
+    // The MFMA operands.  bf16 pools: the loaded registers themselves.  e4m3 pools: load L of
+    // K holds dims 16*(4L + c) .. +15 of token tau(n), which feed steps 2L and 2L + 1 (the
+    // contraction order is free as long as q follows it, see below); load e of V holds dims
+    // 8n .. 8n+7 of token 4e + c as eight bytes.
+    u32x4 k[kKSteps];
+    VOp v[kFp8 ? 4 : kVLoads];
+    if constexpr (kFp8) {
+#pragma unroll
+      for (int jj = 0; jj < kKSteps; ++jj) {
+        const u32x2 a2 = widen_e4m3x4(kraw[jj >> 1][2 * (jj & 1)]);
+        const u32x2 b2 = widen_e4m3x4(kraw[jj >> 1][2 * (jj & 1) + 1]);
+        k[jj] = u32x4{a2.x, a2.y, b2.x, b2.y};
+      }
+#pragma unroll
+      for (int e = 0; e < 4; ++e) {
+        const u32x2 a2 = widen_e4m3x4(vraw[e].x), b2 = widen_e4m3x4(vraw[e].y);
+        v[e] = VOp{a2.x, a2.y, b2.x, b2.y};
+      }
+    } else {
+#pragma unroll
+      for (int jj = 0; jj < kKSteps; ++jj) k[jj] = kraw[jj];
+#pragma unroll
+      for (int e = 0; e < kVLoads; ++e) v[e] = vraw[e];
+    }
     const int meta = __builtin_amdgcn_readlane(dA.meta, idx);
     const int ntok = meta & 0xff;
 
@@ -284,10 +324,12 @@ __global__ __launch_bounds__(kStreamWavesPerGroup * 64) void attn_stream_kernel(
       // A new (request, KV head): fetch its query group.
       seg_open = false;
       const int qrow = __builtin_amdgcn_readlane(dA.qrow, idx);
-      const u32x4* qp = (const u32x4*)(a.q + (int64_t)(qrow + min(n, G - 1)) * kD) + c;
+      const u32x4* qrow_p = (const u32x4*)(a.q + (int64_t)(qrow + min(n, G - 1)) * kD);
 #pragma unroll
       for (int jj = 0; jj < kKSteps; ++jj) {
-        const u32x4 wq = qp[4 * jj];
+        // dims of step jj in this lane: 32*jj + 8*c .. +7, or, following the byte order of an
+        // e4m3 K load, 64*(jj/2) + 16*c + 8*(jj%2) .. +7
+        const u32x4 wq = kFp8 ? qrow_p[8 * (jj >> 1) + 2 * c + (jj & 1)] : qrow_p[4 * jj + c];
         qop[jj] = (n < G) ? wq : u32x4{0, 0, 0, 0};
       }
     }
@@ -310,8 +352,8 @@ __global__ __launch_bounds__(kStreamWavesPerGroup * 64) void attn_stream_kernel(
         valid[e] = 4 * e + c < ntok;
         x[e] = valid[e] ? x[e] : kNegInf;
         if (!valid[e]) {
-          if (kD == 256) { v[2 * e] = VReg{}; v[2 * e + 1] = VReg{}; }
-          else v[e] = VReg{};
+          if (kD == 256) { v[2 * e] = VOp{}; v[2 * e + 1] = VOp{}; }
+          else v[e] = VOp{};
         }
       }
     }
@@ -421,7 +463,7 @@ __global__ __launch_bounds__(kStreamWavesPerGroup * 64) void attn_stream_kernel(
 
   // A ring of kRing register buffers: kRing - 1 blocks are always in flight
   // while one is consumed, and no buffer is ever copied.
-  u32x4 kbuf[kRing][kKSteps];
+  u32x4 kbuf[kRing][kKLoads];
   VReg vbuf[kRing][kVLoads];
 #pragma unroll
   for (int i = 0; i < kRing - 1; ++i) issue(kbuf[i], vbuf[i], i);
@@ -460,9 +502,12 @@ hipError_t launch_attn_stream(const AttnLaunch& a_in, hipStream_t stream) {
   if (a.rec_buffered < 1) return hipErrorInvalidValue;
   const size_t lds = cum_bytes + (size_t)kStreamWavesPerGroup * a.rec_buffered * rec_bytes;
   const dim3 grid(a.waves / kStreamWavesPerGroup), block(kStreamWavesPerGroup * 64);
-  if (a.D == 64) hipLaunchKernelGGL(attn_stream_kernel<64>, grid, block, lds, stream, a);
-  else if (a.D == 128) hipLaunchKernelGGL(attn_stream_kernel<128>, grid, block, lds, stream, a);
-  else if (a.D == 256) hipLaunchKernelGGL(attn_stream_kernel<256>, grid, block, lds, stream, a);
+  if (a.kv_fp8) {
+    if (a.D != 128) return hipErrorInvalidValue;
+    hipLaunchKernelGGL((attn_stream_kernel<128, true>), grid, block, lds, stream, a);
+  } else if (a.D == 64) hipLaunchKernelGGL((attn_stream_kernel<64, false>), grid, block, lds, stream, a);
+  else if (a.D == 128) hipLaunchKernelGGL((attn_stream_kernel<128, false>), grid, block, lds, stream, a);
+  else if (a.D == 256) hipLaunchKernelGGL((attn_stream_kernel<256, false>), grid, block, lds, stream, a);
   else return hipErrorInvalidValue;
   return hipGetLastError();
 }

@@ -188,6 +188,8 @@ static int prepare_attn(const int32_t* block_tables, const int32_t* context_lens
   a->max_ctx = g.max_ctx;
   a->NB = (int)shape->num_pool_blocks;
   a->scale_log2e = scale * 1.4426950408889634f;
+  a->out_scale = 1.f;
+  a->kv_fp8 = 0;
   const WorkspaceLayout lay = workspace_layout(shape, g);
   char* ws = static_cast<char*>(workspace);
   a->ws_rec = reinterpret_cast<float*>(ws);
@@ -205,8 +207,8 @@ static int check_layer_pointers(const void* q, const void* k_pool, const void* v
 static int launch_layer(pkv::AttnLaunch& a, const void* q, const void* k_pool, const void* v_pool,
                         void* out, hipStream_t st) {
   a.q = static_cast<const uint16_t*>(q);
-  a.k_pool = static_cast<const uint16_t*>(k_pool);
-  a.v_pool = static_cast<const uint16_t*>(v_pool);
+  a.k_pool = k_pool;
+  a.v_pool = v_pool;
   a.out = static_cast<uint16_t*>(out);
   hipError_t e = pkv::launch_attn_stream(a, st);
   if (e != hipSuccess) return launch_status(e);
@@ -226,6 +228,30 @@ int paged_decode_attn(const void* q, const void* k_pool, const void* v_pool,
   if (rc != PKV_OK || empty) return rc;
   rc = check_layer_pointers(q, k_pool, v_pool, out);
   if (rc != PKV_OK) return rc;
+  return launch_layer(a, q, k_pool, v_pool, out, static_cast<hipStream_t>(stream));
+}
+
+int paged_decode_attn_fp8kv(const void* q, const void* k_pool, const void* v_pool,
+                            const int32_t* block_tables, const int32_t* context_lens, float scale,
+                            float k_scale, float v_scale, void* out, const pkv_attn_shape* shape,
+                            void* workspace, size_t workspace_bytes_given, void* stream) {
+  pkv::AttnLaunch a;
+  bool empty = false;
+  int rc = prepare_attn(block_tables, context_lens, scale, shape, workspace, workspace_bytes_given,
+                        &a, &empty);
+  if (rc != PKV_OK) return rc;
+  if (shape->head_dim != 128) return PKV_ERR_SHAPE;   // the one-byte pool layout is built for D = 128
+  if (!(k_scale > 0.f) || !(v_scale > 0.f) || !(k_scale < __builtin_inff()) ||
+      !(v_scale < __builtin_inff()))
+    return PKV_ERR_SHAPE;
+  if (empty) return PKV_OK;
+  rc = check_layer_pointers(q, k_pool, v_pool, out);
+  if (rc != PKV_OK) return rc;
+  // K = k_scale * e4m3: the factor joins the softmax scale; V = v_scale * e4m3: applied once
+  // to the normalised row
+  a.scale_log2e = scale * k_scale * 1.4426950408889634f;
+  a.out_scale = v_scale;
+  a.kv_fp8 = 1;
   return launch_layer(a, q, k_pool, v_pool, out, static_cast<hipStream_t>(stream));
 }
 
@@ -290,6 +316,29 @@ int kv_append(const void* k_new, const void* v_new, void* k_pool, void* v_pool,
       shape->num_seqs, shape->num_kv_heads, shape->head_dim, shape->max_blocks_per_seq,
       shape->block_size, g.max_ctx, (int)shape->num_pool_blocks, g_id_faults,
       static_cast<hipStream_t>(stream));
+  return launch_status(e);
+}
+
+int kv_append_fp8(const void* k_new, const void* v_new, void* k_pool, void* v_pool,
+                  const int32_t* block_tables, const int32_t* context_lens, float k_scale,
+                  float v_scale, const pkv_attn_shape* shape, void* stream) {
+  Geometry g;
+  const int rc = check_shape(shape, &g);
+  if (rc != PKV_OK) return rc;
+  if (shape->head_dim != 128) return PKV_ERR_SHAPE;
+  if (!(k_scale > 0.f) || !(v_scale > 0.f) || !(k_scale < __builtin_inff()) ||
+      !(v_scale < __builtin_inff()))
+    return PKV_ERR_SHAPE;
+  if (shape->num_seqs == 0) return PKV_OK;
+  if (!k_new || !v_new || !k_pool || !v_pool || !block_tables || !context_lens) return PKV_ERR_NULL;
+  if (misaligned16(k_new) || misaligned16(v_new) || misaligned16(k_pool) || misaligned16(v_pool) ||
+      (reinterpret_cast<uintptr_t>(block_tables) & 3u) || (reinterpret_cast<uintptr_t>(context_lens) & 3u))
+    return PKV_ERR_ALIGN;
+  const hipError_t e = pkv::launch_kv_append_fp8(
+      static_cast<const uint16_t*>(k_new), static_cast<const uint16_t*>(v_new), k_pool, v_pool,
+      block_tables, context_lens, k_scale, v_scale, shape->num_seqs, shape->num_kv_heads,
+      shape->head_dim, shape->max_blocks_per_seq, shape->block_size, g.max_ctx,
+      (int)shape->num_pool_blocks, g_id_faults, static_cast<hipStream_t>(stream));
   return launch_status(e);
 }
 

@@ -56,14 +56,16 @@ __host__ __device__ inline int record_floats(int G, int D) { return G * D + 2 * 
 
 struct AttnLaunch {
   const uint16_t* q;
-  const uint16_t* k_pool;
-  const uint16_t* v_pool;
+  const void* k_pool;   // bf16, or e4m3 bytes when kv_fp8
+  const void* v_pool;
   const int32_t* block_tables;
   const int32_t* context_lens;
   uint16_t* out;
   float* ws_rec;   // [slots][record_floats(G)] partial records, see record_floats()
   int32_t* ws_cum; // [S + 1] cumB, written by the stream pass for the merge
-  float scale_log2e;
+  float scale_log2e;   // softmax scale x log2(e) (x the K pool's scale for an e4m3 pool)
+  float out_scale;     // applied to the normalised row: 1, or the V pool's scale
+  int kv_fp8;          // the pools hold one-byte e4m3 values (D = 128 only)
   int32_t* id_faults;  // optional device counter of refused block ids (nullptr: not reported)
   int S, Hq, Hkv, G, MAXB;
   int D;           // head dimension: 64, 128 or 256
@@ -98,5 +100,12 @@ hipError_t launch_kv_append(const uint16_t* k_new, const uint16_t* v_new, uint16
                             uint16_t* v_pool, const int32_t* block_tables,
                             const int32_t* context_lens, int S, int Hkv, int D, int MAXB, int B,
                             int max_ctx, int NB, int32_t* id_faults, hipStream_t stream);
+
+// The same for one-byte E4M3 pools: rows are divided by the pool's scale and rounded to E4M3.
+hipError_t launch_kv_append_fp8(const uint16_t* k_new, const uint16_t* v_new, void* k_pool,
+                                void* v_pool, const int32_t* block_tables,
+                                const int32_t* context_lens, float k_scale, float v_scale, int S,
+                                int Hkv, int D, int MAXB, int B, int max_ctx, int NB,
+                                int32_t* id_faults, hipStream_t stream);
 
 }  // namespace pkv

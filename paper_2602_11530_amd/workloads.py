@@ -52,6 +52,18 @@ def normal_bf16(rng: np.random.Generator, shape) -> np.ndarray:
     return f32_to_bf16_bits(rng.standard_normal(size=shape, dtype=np.float32))
 
 
+def normal_e4m3(rng: np.random.Generator, shape, pool_scale: float) -> np.ndarray:
+    """E4M3 bytes (uint8) of N(0,1) draws divided by ``pool_scale``: the 8-bit image of a pool
+    whose values are ``pool_scale * e4m3(byte)``.  The rounding is the library routine's
+    (torch's float8_e4m3fn conversion); draws are clipped to the format's range first."""
+    import torch
+    x = rng.standard_normal(size=shape, dtype=np.float32) / np.float32(pool_scale)
+    x = np.clip(x, -448.0, 448.0)
+    return torch.from_numpy(x).to(torch.float8_e4m3fn).view(torch.uint8).numpy()
+
+
+E4M3_NAN = np.uint8(0x7F)
+E4M3_NAN_NEG = np.uint8(0xFF)
 BF16_NAN = np.uint16(0x7FC0)
 BF16_INF = np.uint16(0x7F80)
 
@@ -291,6 +303,29 @@ def make_host_tensors(w: Workload, layer: int = 0, poison_unused: bool = False):
         mask = ~valid
         k[mask[:, None, :, None].repeat(w.num_kv_heads, 1).repeat(w.head_dim, 3)] = BF16_NAN
         v[mask[:, None, :, None].repeat(w.num_kv_heads, 1).repeat(w.head_dim, 3)] = BF16_INF
+    return q, k, v
+
+
+def make_host_tensors_fp8(w: Workload, k_scale: float, v_scale: float, layer: int = 0,
+                          poison_unused: bool = False):
+    """q as bf16 bit patterns, K pool and V pool as E4M3 bytes (uint8) such that
+    scale * e4m3(byte) ~ N(0,1).  ``poison_unused`` fills every slot no request may read with
+    the format's two NaN bytes."""
+    rng = np.random.default_rng(w.seed + 1000 * layer + 19)
+    q = normal_bf16(rng, w.q_shape())
+    k = normal_e4m3(rng, w.pool_shape(), k_scale)
+    v = normal_e4m3(rng, w.pool_shape(), v_scale)
+    if poison_unused:
+        valid = np.zeros((w.num_pool_blocks, w.block_size), dtype=bool)
+        used = w.used_blocks()
+        for s in range(w.num_seqs):
+            L = int(w.context_lens[s])
+            for j in range(int(used[s])):
+                n = min(w.block_size, L - j * w.block_size)
+                valid[w.block_tables[s, j], :n] = True
+        mask = (~valid)[:, None, :, None].repeat(w.num_kv_heads, 1).repeat(w.head_dim, 3)
+        k[mask] = E4M3_NAN
+        v[mask] = E4M3_NAN_NEG
     return q, k, v
 
 

@@ -1,0 +1,223 @@
+"""Attention over 8-bit (E4M3) KV pools: one byte per element, one fp32 scale per pool, q and
+out in bf16.  Same parity bar as the bf16 call, against the oracle run on the same bytes."""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+from paper_2602_11530_amd import binding as pkv
+from paper_2602_11530_amd import workloads as wl
+
+from gpu_util import MAX_ABS, REL_L2, abs_error_within_bar, assert_launchable, shape_of, to_bits, to_dev
+
+pytestmark = pytest.mark.gpu
+
+EDGE = [1, 15, 16, 17, 31, 32, 33, 47, 48, 49, 63, 64, 65, 0, 127, 128, 129, 511, 512, 513, 1000, 2]
+KS, VS = np.float32(0.0134), np.float32(0.0171)     # 448 * scale ~ 6 and 7.7 sigma of N(0,1)
+
+
+def dev8(a):
+    return torch.from_numpy(np.ascontiguousarray(a)).to("cuda:0")
+
+
+def run_fp8(w, q, k8, v8, k_scale=KS, v_scale=VS, partition_size=None, scale=None, tables=None):
+    assert k8.dtype == np.uint8 and tuple(k8.shape) == w.pool_shape() == tuple(v8.shape)
+    assert_launchable(w)
+    shape = shape_of(w, partition_size)
+    ws = torch.empty(max(pkv.pkv_attn_workspace_bytes(shape), 16), dtype=torch.uint8, device="cuda:0")
+    out = torch.full(w.q_shape(), 0x7FC1, dtype=torch.int16, device="cuda:0")
+    pkv.paged_decode_attn_fp8kv(to_dev(q), dev8(k8), dev8(v8), to_dev(w.block_tables if tables is None else tables),
+                                to_dev(w.context_lens), float(w.scale if scale is None else scale),
+                                float(k_scale), float(v_scale), out, shape, ws)
+    torch.cuda.synchronize()
+    return to_bits(out)
+
+
+def check(w, q, k8, v8, got, what, k_scale=KS, v_scale=VS):
+    ref = oracle.paged_decode_attn_fp8kv(q, k8, v8, w.block_tables, w.context_lens, w.scale, k_scale, v_scale)
+    c = oracle.compare(got, ref)
+    print(f"{what}: {c}", flush=True)
+    assert np.isfinite(wl.bf16_bits_to_f64(got)).all()
+    assert c["rel_l2"] <= REL_L2 and c["worst_seq_rel_l2"] <= 2 * REL_L2, c
+    assert abs_error_within_bar(got, ref), c
+
+
+def test_every_byte_decodes_as_e4m3(device):
+    """A one-token context returns v_scale * (its V row) exactly: rows holding all 254 finite bytes
+    show that the device reads the bytes as OCP E4M3 (bias 7, subnormals, +-448), bit for bit."""
+    w = wl.custom([1, 1], 2, 2, seed=3, num_pool_blocks=4)
+    q, k8, v8 = wl.make_host_tensors_fp8(w, KS, VS)
+    codes = np.arange(256, dtype=np.uint8)
+    codes[[0x7F, 0xFF]] = 0
+    for s in range(2):
+        v8[w.block_tables[s, 0], :, 0, :] = codes.reshape(2, 128) if s == 0 else codes[::-1].reshape(2, 128)
+    for v_scale in (1.0, 0.5, 4.0):          # powers of two keep the product exact in bf16
+        got = wl.bf16_bits_to_f64(run_fp8(w, q, k8, v8, v_scale=v_scale)).reshape(w.q_shape())
+        want = np.array([[v_scale * oracle.e4m3(b) for b in v8[w.block_tables[s, 0], h, 0]]
+                         for s in range(2) for h in range(2)]).reshape(w.q_shape())
+        assert np.array_equal(got, want)
+
+
+@pytest.mark.parametrize("B", [16, 32, 64])
+@pytest.mark.parametrize("P", [0, 64, 512])
+def test_edge_lengths(device, B, P):
+    for hq, hkv in [(40, 8), (8, 2), (16, 1), (7, 7)]:
+        w = wl.custom(EDGE, hq, hkv, seed=900 + B + hq, num_pool_blocks=300, partition_size=P, block_size=B)
+        q, k8, v8 = wl.make_host_tensors_fp8(w, KS, VS, poison_unused=True)
+        print(f"fp8 B={B} P={P} hq={hq} hkv={hkv}", flush=True)
+        got = run_fp8(w, q, k8, v8)
+        check(w, q, k8, v8, got, f"fp8 B={B} hq={hq} hkv={hkv} P={P}")
+        assert not got.reshape(w.q_shape())[EDGE.index(0)].any()
+
+
+def test_invariances(device):
+    """Physical block permutation: bitwise.  Partition size: within tolerance.  The scales act as
+    factors: (scale, 4 k_scale) equals (4 scale, k_scale) bit for bit (the product is formed once,
+    in fp32, on the host), and a v_scale of 2 doubles every output exactly."""
+    lens = [1300, 77, 2048, 640, 33, 4100]
+    w = wl.custom(lens, 40, 8, seed=5)
+    q, k8, v8 = wl.make_host_tensors_fp8(w, KS, VS)
+    base = run_fp8(w, q, k8, v8)
+    rng = np.random.default_rng(9)
+    perm = rng.permutation(w.num_pool_blocks).astype(np.int32)
+    k2, v2 = np.empty_like(k8), np.empty_like(v8)
+    k2[perm], v2[perm] = k8, v8
+    tables2 = np.where(w.block_tables >= 0, perm[np.maximum(w.block_tables, 0)], -1).astype(np.int32)
+    w2 = wl.Workload("perm", 40, 8, w.context_lens, tables2, w.num_pool_blocks, seed=w.seed)
+    assert np.array_equal(run_fp8(w2, q, k2, v2), base)
+    ref = oracle.paged_decode_attn_fp8kv(q, k8, v8, w.block_tables, w.context_lens, w.scale, KS, VS)
+    for P in (16, 128, 512, 4096):
+        c = oracle.compare(run_fp8(w, q, k8, v8, partition_size=P), ref)
+        assert c["max_abs"] <= MAX_ABS and c["rel_l2"] <= REL_L2, (P, c)
+    a = run_fp8(w, q, k8, v8, k_scale=4 * KS, scale=float(w.scale) / 4)
+    assert np.array_equal(a, base)
+    doubled = wl.bf16_bits_to_f64(run_fp8(w, q, k8, v8, v_scale=2 * VS))
+    assert np.array_equal(doubled, 2 * wl.bf16_bits_to_f64(base))
+
+
+def test_migration_of_an_8bit_pool_keeps_attention_bitwise(device):
+    """The copies take an E4M3 pool as it is (16 KiB blocks): gather + scatter into other ids,
+    tables rewritten, attention unchanged bit for bit."""
+    w = wl.custom([700, 45, 1300, 16, 333], 40, 8, seed=23, num_pool_blocks=400)
+    q, k8, v8 = wl.make_host_tensors_fp8(w, KS, VS)
+    before = run_fp8(w, q, k8, v8)
+    mig = wl.make_migration(w, 0.4)
+    n, bb, NB = len(mig.old_ids), w.block_bytes // 2, w.num_pool_blocks
+    old_d, new_d = to_dev(mig.old_ids), to_dev(mig.new_ids)
+    pools = []
+    for pool in (k8, v8):
+        p_d = dev8(pool)
+        st = torch.empty((n,) + pool.shape[1:], dtype=torch.uint8, device="cuda:0")
+        pkv.kv_blocks_gather(p_d, old_d, st, n, bb, NB)
+        pkv.kv_blocks_scatter(st, p_d, new_d, n, bb, NB)
+        torch.cuda.synchronize()
+        want = oracle.kv_blocks_scatter(oracle.kv_blocks_gather(pool, mig.old_ids), pool, mig.new_ids)
+        got = p_d.cpu().numpy()
+        assert np.array_equal(got, want)
+        pools.append(got)
+    w_after = wl.Workload("after", 40, 8, w.context_lens, mig.tables_after, NB, seed=w.seed)
+    assert np.array_equal(run_fp8(w_after, q, pools[0], pools[1]), before)
+
+
+def test_argument_errors(device):
+    w = wl.custom([40, 17], 8, 2, seed=1, num_pool_blocks=8)
+    q, k8, v8 = wl.make_host_tensors_fp8(w, KS, VS)
+    args = [to_dev(q), dev8(k8), dev8(v8), to_dev(w.block_tables), to_dev(w.context_lens)]
+    out = torch.zeros(w.q_shape(), dtype=torch.int16, device="cuda:0")
+    shape = shape_of(w)
+    ws = torch.empty(pkv.pkv_attn_workspace_bytes(shape), dtype=torch.uint8, device="cuda:0")
+    for ks, vs in [(0.0, 1.0), (1.0, -1.0), (float("nan"), 1.0), (1.0, float("inf"))]:
+        with pytest.raises(pkv.PkvError) as e:
+            pkv.paged_decode_attn_fp8kv(*args, 0.1, ks, vs, out, shape, ws)
+        assert e.value.status == pkv.PKV_ERR_SHAPE
+    shape64 = pkv.make_shape(2, 8, 2, w.max_blocks_per_seq, 8, head_dim=64)
+    with pytest.raises(pkv.PkvError) as e:
+        pkv.paged_decode_attn_fp8kv(*args, 0.1, 1.0, 1.0, out, shape64, ws)
+    assert e.value.status == pkv.PKV_ERR_SHAPE
+
+
+def test_config2_in_8_bits(device):
+    """The Qwen-32B-shaped batch with E4M3 pools: full oracle parity, and the rate it streams at
+    (half the KV bytes of the bf16 batch)."""
+    w = wl.cfg2_qwen32b()
+    assert_launchable(w)
+    g = torch.Generator(device=device)
+    g.manual_seed(w.seed + 19)
+    q = torch.randn(w.q_shape(), generator=g, device=device, dtype=torch.float32).to(torch.bfloat16)
+    mk = lambda s: (torch.randn(w.pool_shape(), generator=g, device=device, dtype=torch.float32) / float(s)) \
+        .clamp_(-448.0, 448.0).to(torch.float8_e4m3fn).view(torch.uint8)
+    k8, v8 = mk(KS), mk(VS)
+    t_d, l_d = to_dev(w.block_tables), to_dev(w.context_lens)
+    mc = int(w.context_lens.max())
+    shape = shape_of(w, None, mc)
+    ws = torch.empty(pkv.pkv_attn_workspace_bytes(shape), dtype=torch.uint8, device=device)
+    out = torch.full(w.q_shape(), 0x7FC1, dtype=torch.int16, device=device)
+    call = lambda: pkv.paged_decode_attn_fp8kv(q, k8, v8, t_d, l_d, float(w.scale), float(KS), float(VS),
+                                               out, shape, ws)
+    call()
+    torch.cuda.synchronize()
+    a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    reps = 20
+    a.record()
+    for _ in range(reps):
+        call()
+    b.record()
+    torch.cuda.synchronize()
+    ms = a.elapsed_time(b) / reps
+    nbytes = w.attn_algorithmic_bytes() - w.total_tokens * w.num_kv_heads * w.head_dim * 2   # KV at 1 B
+    print(f"\nfp8 KV: {nbytes / 1e9:.3f} GB in {ms:.4f} ms = {nbytes / ms / 1e6:.0f} GB/s, "
+          f"{w.total_tokens / ms / 1e6:.3f} G tokens attended/s", flush=True)
+    check(w, to_bits(q), k8.cpu().numpy(), v8.cpu().numpy(), to_bits(out), "cfg2 with E4M3 pools")
+
+
+def test_append_quantises_bit_exactly(device):
+    """kv_append_fp8 equals the oracle byte for byte: ordinary rows, rows that saturate, values on
+    and next to the rounding boundaries of the format, zeros of both signs."""
+    w = wl.custom([1, 16, 17, 0, 300, 33, 512, 513], 40, 8, seed=41, num_pool_blocks=120)
+    rng = np.random.default_rng(8)
+    _, k8, v8 = wl.make_host_tensors_fp8(w, KS, VS)
+    k_new, v_new = wl.normal_bf16(rng, (w.num_seqs, 8, 128)), wl.normal_bf16(rng, (w.num_seqs, 8, 128))
+    # midpoints between neighbouring E4M3 values (times the scale) and their bf16 neighbours
+    grid = np.array(sorted({oracle.e4m3(b) for b in range(0x7F)}))
+    mids = ((grid[1:] + grid[:-1]) / 2)[:120]
+    for s, scale, new in ((1, float(KS), k_new), (2, float(VS), v_new)):
+        vals = wl.f32_to_bf16_bits((mids * scale).astype(np.float32))
+        new[s, 0, :120] = vals
+        new[s, 1, :120] = vals + np.uint16(1)
+        new[s, 2, :120] = vals - np.uint16(1)
+        new[s, 3, :8] = wl.f32_to_bf16_bits(np.float32([100.0, -100.0, 0.0, -0.0, 6.5, -6.5, 1e-6, 448 * scale]))
+    k_d, v_d = dev8(k8), dev8(v8)
+    pkv.kv_append_fp8(to_dev(k_new), to_dev(v_new), k_d, v_d, to_dev(w.block_tables),
+                      to_dev(w.context_lens), float(KS), float(VS), shape_of(w))
+    torch.cuda.synchronize()
+    wk, wv = oracle.kv_append_fp8(k_new, v_new, k8, v8, w.block_tables, w.context_lens, KS, VS)
+    assert np.array_equal(k_d.cpu().numpy(), wk)
+    assert np.array_equal(v_d.cpu().numpy(), wv)
+    assert (wk != k8).sum() > 1000      # the call did write rows
+
+
+def test_decode_loop_append_then_attend(device):
+    """Three decode steps on 8-bit pools: the new rows are quantised and appended by the library,
+    attention is checked against the oracle run on pools the oracle appended to itself."""
+    final = np.array([20, 48, 515, 1300, 3], np.int32)
+    w = wl.custom(final, 40, 8, seed=77, num_pool_blocks=160)
+    rng = np.random.default_rng(5)
+    _, k8, v8 = wl.make_host_tensors_fp8(w, KS, VS)
+    k_d, v_d, t_d = dev8(k8), dev8(v8), to_dev(w.block_tables)
+    k_h, v_h = k8.copy(), v8.copy()
+    shape = shape_of(w)
+    ws = torch.empty(pkv.pkv_attn_workspace_bytes(shape), dtype=torch.uint8, device="cuda:0")
+    for back in (2, 1, 0):
+        w.context_lens = final - back
+        assert_launchable(w)
+        k_new, v_new = wl.normal_bf16(rng, (w.num_seqs, 8, 128)), wl.normal_bf16(rng, (w.num_seqs, 8, 128))
+        q = wl.normal_bf16(rng, w.q_shape())
+        lens_d = to_dev(w.context_lens)
+        out = torch.full(w.q_shape(), 0x7FC1, dtype=torch.int16, device="cuda:0")
+        pkv.kv_append_fp8(to_dev(k_new), to_dev(v_new), k_d, v_d, t_d, lens_d, float(KS), float(VS), shape)
+        pkv.paged_decode_attn_fp8kv(to_dev(q), k_d, v_d, t_d, lens_d, float(w.scale), float(KS), float(VS),
+                                    out, shape, ws)
+        torch.cuda.synchronize()
+        k_h, v_h = oracle.kv_append_fp8(k_new, v_new, k_h, v_h, w.block_tables, w.context_lens, KS, VS)
+        assert np.array_equal(k_d.cpu().numpy(), k_h) and np.array_equal(v_d.cpu().numpy(), v_h)
+        check(w, q, k_h, v_h, to_bits(out), f"fp8 append step -{back}")

@@ -420,3 +420,134 @@ def test_compare_rejects_wrong_outputs_at_the_bar():
     bits[0, 0, :4] ^= np.uint16(0x0040)                       # flips a mantissa bit: ~25-50 % off
     c = oracle.compare(bits, ref)
     assert c["worst_seq_rel_l2"] > 5e-3 and c["worst_seq_rel_l2"] > c["rel_l2"]
+
+
+# ---- 8-bit (E4M3) KV pools --------------------------------------------------------------
+
+def e4m3_values(bits: np.ndarray) -> np.ndarray:
+    """The library's decode of E4M3 bytes (torch's float8_e4m3fn), as float64."""
+    return torch.from_numpy(np.ascontiguousarray(bits)).view(torch.float8_e4m3fn).to(torch.float64).numpy()
+
+
+def test_e4m3_decode_every_byte():
+    got = np.array([oracle.e4m3(b) for b in range(256)])
+    want = e4m3_values(np.arange(256, dtype=np.uint8))
+    nan = np.isnan(want)
+    assert sorted(np.nonzero(nan)[0].tolist()) == [0x7F, 0xFF]
+    assert np.array_equal(np.isnan(got), nan)
+    assert np.array_equal(got[~nan], want[~nan])
+    assert np.array_equal(np.signbit(got[~nan]), np.signbit(want[~nan]))
+    # the format's landmarks, written out: 1, the largest finite value, the smallest subnormal,
+    # the smallest normal, and the seven subnormals m * 2^-9
+    assert oracle.e4m3(0x38) == 1.0 and oracle.e4m3(0x7E) == 448.0 and oracle.e4m3(0xFE) == -448.0
+    assert oracle.e4m3(0x01) == 2.0 ** -9 and oracle.e4m3(0x08) == 2.0 ** -6
+    assert [oracle.e4m3(m) for m in range(8)] == [m * 2.0 ** -9 for m in range(8)]
+    assert oracle.e4m3(0x3C) == 1.5 and oracle.e4m3(0x40) == 2.0 and oracle.e4m3(0xC0) == -2.0
+
+
+def brute_force_values(w, qf, Kf, Vf, scale):
+    """Dense softmax(scale * q K^T) V on pools given as float64 values."""
+    out = np.zeros(w.q_shape(), dtype=np.float64)
+    G = w.num_q_heads // w.num_kv_heads
+
+    def rows(pool, s):
+        L = int(w.context_lens[s])
+        nb = (L + w.block_size - 1) // w.block_size
+        blocks = pool[w.block_tables[s, :nb]]
+        return np.transpose(blocks, (0, 2, 1, 3)).reshape(nb * w.block_size, w.num_kv_heads, w.head_dim)[:L]
+
+    for s in range(w.num_seqs):
+        if w.context_lens[s] == 0:
+            continue
+        K, V = rows(Kf, s), rows(Vf, s)
+        for h in range(w.num_q_heads):
+            x = float(np.float32(scale)) * (K[:, h // G, :] @ qf[s, h])
+            p = np.exp(x - x.max())
+            out[s, h] = (p / p.sum()) @ V[:, h // G, :]
+    return out
+
+
+@pytest.mark.parametrize("B", [16, 64])
+def test_fp8kv_attention_against_brute_force(B):
+    ks, vs = np.float32(0.013), np.float32(0.021)
+    w = wl.custom([33, 1, 0, 257, 16, 700, 15], 10, 2, seed=61, num_pool_blocks=90, block_size=B)
+    q, k8, v8 = wl.make_host_tensors_fp8(w, ks, vs, poison_unused=True)
+    assert k8.dtype == np.uint8 and (k8 == 0x7F).any() and (v8 == 0xFF).any()
+    ref = oracle.paged_decode_attn_fp8kv(q, k8, v8, w.block_tables, w.context_lens, w.scale, ks, vs)
+    assert np.isfinite(ref).all() and not ref[2].any()
+    qf = wl.bf16_bits_to_f64(q).reshape(w.q_shape())
+    Kf = np.nan_to_num(e4m3_values(k8)) * float(ks)       # the poison never enters a valid row
+    Vf = np.nan_to_num(e4m3_values(v8)) * float(vs)
+    bf = brute_force_values(w, qf, Kf, Vf, w.scale)
+    assert np.abs(ref - bf).max() < 1e-12
+    # the values really are a unit-variance pool seen through the scales
+    assert 0.9 < Kf[w.block_tables[5, 0], :, :, :].std() < 1.1
+
+
+def test_fp8kv_equals_bf16_function_on_the_same_values():
+    """Every E4M3 value is a bf16 value: with unit scales the 8-bit function and the bf16
+    function must agree on a pool holding the same numbers; and the scales act as factors on
+    the scores and on the output."""
+    w = wl.custom([300, 45, 1, 64], 12, 4, seed=62, num_pool_blocks=40)
+    q, k8, v8 = wl.make_host_tensors_fp8(w, 0.02, 0.02)
+    as_bf16 = lambda b: torch.from_numpy(e4m3_values(b)).to(torch.bfloat16).view(torch.int16).numpy().view(np.uint16)
+    kb, vb = as_bf16(k8), as_bf16(v8)
+    assert np.array_equal(wl.bf16_bits_to_f64(kb), e4m3_values(k8))     # the widening is exact
+    a = oracle.paged_decode_attn_fp8kv(q, k8, v8, w.block_tables, w.context_lens, 0.01, 1.0, 1.0)
+    b = oracle.paged_decode_attn(q, kb, vb, w.block_tables, w.context_lens, 0.01)
+    assert np.abs(a - b).max() < 1e-13 * np.abs(b).max()
+    # k_scale multiplies the scores: (scale, 4 k) == (4 scale, k); v_scale multiplies the rows
+    c = oracle.paged_decode_attn_fp8kv(q, k8, v8, w.block_tables, w.context_lens, 0.0025, 4.0, 1.0)
+    assert np.abs(a - c).max() < 1e-13 * np.abs(a).max()
+    d = oracle.paged_decode_attn_fp8kv(q, k8, v8, w.block_tables, w.context_lens, 0.01, 1.0, 3.0)
+    assert np.abs(d - 3.0 * a).max() < 1e-13 * np.abs(a).max()
+    # one token: the row is v_scale times the decoded bytes
+    one = oracle.paged_decode_attn_fp8kv(q, k8, v8, w.block_tables, w.context_lens, 0.01, 1.0, 0.5)
+    assert np.array_equal(one[2, 5], 0.5 * e4m3_values(v8[w.block_tables[2, 0], 5 // 3, 0]))
+
+
+def test_to_e4m3_against_library_rounding():
+    """fp32 -> E4M3 on every finite bf16 value (as fp32) and on a dense set of fp32 values around
+    every rounding boundary: equal to torch's conversion wherever that is finite, and saturated
+    to +-448 where torch overflows to NaN."""
+    bits = np.arange(65536, dtype=np.uint32)
+    vals = (bits << np.uint32(16)).view(np.float32)
+    vals = vals[np.isfinite(vals)]
+    # midpoints between neighbouring E4M3 values, and their fp32 neighbours on either side
+    grid = np.array(sorted({oracle.e4m3(b) for b in range(0x7F)}), dtype=np.float64)
+    mids = ((grid[1:] + grid[:-1]) / 2).astype(np.float32)
+    around = np.concatenate([mids, np.nextafter(mids, np.float32(np.inf)), np.nextafter(mids, np.float32(-np.inf))])
+    vals = np.concatenate([vals, around, -around, np.float32([448, 449, 463.9, 464, 465, 1e9, -1e9, 3e38])])
+    lib = torch.from_numpy(vals).to(torch.float8_e4m3fn).view(torch.uint8).numpy()
+    got = np.array([oracle.to_e4m3(v) for v in vals], dtype=np.uint8)
+    overflow = (lib & 0x7F) == 0x7F
+    assert np.array_equal(got[~overflow], lib[~overflow])
+    assert (np.abs(vals[overflow]) > 448).all()
+    assert np.array_equal(got[overflow], np.where(vals[overflow] > 0, 0x7E, 0xFE).astype(np.uint8))
+    # ties go to the even mantissa: 1.0625 is halfway between 1 (0x38) and 1.125 (0x39)
+    assert oracle.to_e4m3(1.0625) == 0x38 and oracle.to_e4m3(1.1875) == 0x3A
+    assert oracle.to_e4m3(2.0 ** -10) == 0x00 and oracle.to_e4m3(3 * 2.0 ** -10) == 0x02   # subnormal ties
+    assert oracle.to_e4m3(-0.0) == 0x80 and oracle.to_e4m3(float("nan")) & 0x7F == 0x7F
+    # decode(encode(x)) is the nearest grid point
+    for v in np.float32([0.3, -1.7, 5.5, 100.0, 0.004, 447.0]):
+        d = oracle.e4m3(oracle.to_e4m3(v))
+        assert abs(d - v) == np.abs(grid - abs(v)).min()
+
+
+def test_kv_append_fp8_against_indexing():
+    w = wl.custom([1, 16, 17, 0, 300, 33], 12, 4, seed=41, num_pool_blocks=60)
+    rng = np.random.default_rng(8)
+    ks, vs = np.float32(0.0134), np.float32(0.02)
+    _, k8, v8 = wl.make_host_tensors_fp8(w, ks, vs)
+    k_new, v_new = wl.normal_bf16(rng, (w.num_seqs, 4, 128)), wl.normal_bf16(rng, (w.num_seqs, 4, 128))
+    k_new[0, 0, :4] = wl.f32_to_bf16_bits(np.float32([100.0, -100.0, 0.0, 6.0]))   # saturates at 448 * scale
+    ka, va = oracle.kv_append_fp8(k_new, v_new, k8, v8, w.block_tables, w.context_lens, ks, vs)
+    q = lambda x, s: torch.from_numpy(np.clip(wl.bf16_bits_to_f64(x).astype(np.float32) / s, -448, 448)) \
+        .to(torch.float8_e4m3fn).view(torch.uint8).numpy()
+    wk, wv = k8.copy(), v8.copy()
+    for s, L in enumerate(w.context_lens):
+        if L > 0:
+            wk[w.block_tables[s, (L - 1) // 16], :, (L - 1) % 16] = q(k_new[s], ks)
+            wv[w.block_tables[s, (L - 1) // 16], :, (L - 1) % 16] = q(v_new[s], vs)
+    assert np.array_equal(ka, wk) and np.array_equal(va, wv)
+    assert ka[w.block_tables[0, 0], 0, 0, 0] == 0x7E and ka[w.block_tables[0, 0], 0, 0, 1] == 0xFE
