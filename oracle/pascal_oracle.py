@@ -25,10 +25,14 @@ What follows the paper directly (Section IV), in its notation:
 Where the paper is silent this file takes a reading of its own; each is marked
 "reading" where it is applied.  Pins (tests/test_pascal_oracle.py):
 worked tables for both algorithms, the adaptive-migration example of the figure in Section IV-B,
-closed forms for QoE, and invariants of the queue dynamics on seeded traces
-(capacity never exceeded, block ids unique, priority respected, every token
-accounted for).  The queue dynamics beyond those invariants follow readings,
-not printed values: parity unpinned for the exact order of preemptions.
+closed forms for QoE, hand-worked tables for the queue dynamics (a quantum of three
+tokens over seven iterations, circular order under a batch cap, demotion only
+above the threshold, the eviction victim is the last request in round-robin
+order, a_i counts first-quantum answering requests only), and invariants on
+seeded traces and random walks (capacity never exceeded, block ids unique,
+priority respected, every token accounted for).  What stays a reading rather
+than a pinned value: tie-breaks, what counts towards m_i, the allocator's id
+order.
 """
 from __future__ import annotations
 

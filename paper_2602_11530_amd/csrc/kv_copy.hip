@@ -12,16 +12,17 @@ namespace {
 // dirty lines whose write-back slows the kernel that runs next (an attention
 // call measured 17-30 % slower after such a copy).  The staging side depends on
 // the image's size.  An image that fits the 256 MB memory-side cache of an
-// MI355X with room to spare is written with write-through stores and read back
-// with ordinary loads, so that the scatter (or the copy engine) that follows
-// finds it on chip: gather + scatter of 153 MB per pool run 19 % faster that
-// way (6.6 instead of 5.4 TB/s read+write), with no effect on the next kernel.
-// A larger image would only evict itself (5-8 % slower than streaming from
-// about 290 MB on), so it is streamed with nontemporal accesses on both sides.
+// MI355X is written with write-through stores and read back with ordinary
+// loads, so that the scatter (or the copy engine) that follows finds it on
+// chip: gather + scatter of 153 MB per pool run 22 % faster that way (6.66
+// instead of 5.44 TB/s read+write), with no effect on the next kernel.  The
+// gain holds up to an image of about 280 MB, is gone at 310 MB, and beyond that
+// a cached image only evicts itself (8 % slower than streaming at 370 MB), so
+// larger images are streamed with nontemporal accesses on both sides.
 constexpr int kCopyThreads = 256;
 constexpr int kChunksPerThread = 8;                               // 16-byte chunks
 constexpr int kChunksPerGroup = kCopyThreads * kChunksPerThread;  // 32 KiB per workgroup
-constexpr int64_t kCachedStagingBytes = (int64_t)192 << 20;       // staging images up to this size stay on chip
+constexpr int64_t kCachedStagingBytes = (int64_t)256 << 20;       // staging images up to this size stay on chip
 
 enum Policy { kStream, kPlain, kWriteThrough };
 
