@@ -32,9 +32,10 @@ def fill_layer(w, layer, device):
     return q, pools[0], pools[1]
 
 
-def layers_that_fit(w, device, want, reserve_gb=24):
+def layers_that_fit(w, device, want, reserve_gb=24, extra_per_layer=0):
+    torch.cuda.empty_cache()
     free, _ = torch.cuda.mem_get_info(device)
-    per_layer = 2 * w.num_pool_blocks * w.block_bytes + (2 << 20)
+    per_layer = 2 * w.num_pool_blocks * w.block_bytes + (2 << 20) + extra_per_layer
     fit = int((free - (reserve_gb << 30)) // per_layer)
     return max(1, min(want, fit))
 
@@ -139,8 +140,9 @@ def test_cfg5_migration_next_to_decode(device):
     and scatter them into reshuffled ids on stream A, while stream B runs decode
     attention for the surviving 75 % of the batch.  Migrated blocks are bit-exact,
     every other block untouched, the survivors' rows identical to a run without
-    migration, and attention after the move matches the oracle."""
-    n_layers = 6
+    migration, and attention after the move matches the oracle.  All 64 layers when the free
+    HBM allows (pools, plus a copy of the victims' blocks per layer to compare with)."""
+    n_layers = 64
     w = wl.cfg4_phase_mixed(num_layers=n_layers)
     mig = wl.make_migration(w, 0.25)
     assert len(mig.victims) == 24 and len(mig.survivors) == 72
@@ -152,7 +154,10 @@ def test_cfg5_migration_next_to_decode(device):
     assert len(np.unique(mig.new_ids)) == len(mig.new_ids)
     assert mig.old_ids.max() < w.num_pool_blocks and mig.new_ids.max() < w.num_pool_blocks
 
-    n_layers = layers_that_fit(w, device, n_layers)
+    n_layers = layers_that_fit(w, device, n_layers,
+                               extra_per_layer=2 * len(mig.old_ids) * w.block_bytes + (8 << 20))
+    print(f"cfg5: {n_layers} of {w.num_layers} layers resident "
+          f"({n_layers * 2 * w.num_pool_blocks * w.block_bytes / 1e9:.1f} GB of pools)", flush=True)
     layers = [fill_layer(w, l, device) for l in range(n_layers)]
     ws_surv = wl.subset(w, mig.survivors)
     assert_launchable(ws_surv)
