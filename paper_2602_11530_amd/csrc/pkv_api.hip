@@ -235,16 +235,18 @@ int paged_decode_attn_fp8kv(const void* q, const void* k_pool, const void* v_poo
                             const int32_t* block_tables, const int32_t* context_lens, float scale,
                             float k_scale, float v_scale, void* out, const pkv_attn_shape* shape,
                             void* workspace, size_t workspace_bytes_given, void* stream) {
-  pkv::AttnLaunch a;
-  bool empty = false;
-  int rc = prepare_attn(block_tables, context_lens, scale, shape, workspace, workspace_bytes_given,
-                        &a, &empty);
+  Geometry g;
+  int rc = check_shape(shape, &g);
   if (rc != PKV_OK) return rc;
   if (shape->head_dim != 128) return PKV_ERR_SHAPE;   // the one-byte pool layout is built for D = 128
   if (!(k_scale > 0.f) || !(v_scale > 0.f) || !(k_scale < __builtin_inff()) ||
       !(v_scale < __builtin_inff()))
     return PKV_ERR_SHAPE;
-  if (empty) return PKV_OK;
+  pkv::AttnLaunch a;
+  bool empty = false;
+  rc = prepare_attn(block_tables, context_lens, scale, shape, workspace, workspace_bytes_given, &a,
+                    &empty);
+  if (rc != PKV_OK || empty) return rc;
   rc = check_layer_pointers(q, k_pool, v_pool, out);
   if (rc != PKV_OK) return rc;
   // K = k_scale * e4m3: the factor joins the softmax scale; V = v_scale * e4m3: applied once

@@ -214,3 +214,44 @@ def test_move_argument_errors_before_launch():
     assert f(16, 16, 32, None, 4) == pkv.PKV_ERR_NULL
     assert f(16, 16, 24, 16, 4) == pkv.PKV_ERR_ALIGN
     assert f(16, 18, 32, 16, 4) == pkv.PKV_ERR_ALIGN
+
+
+def test_fp8kv_argument_errors_before_launch():
+    L = pkv.lib()
+    sh = pkv.make_shape(4, 8, 2, 19, 128, partition_size=16)
+    need = pkv.pkv_attn_workspace_bytes(sh)
+    f = lambda q=16, k=16, v=16, t=16, l=16, ks=0.01, vs=0.02, o=16, shape=sh, ws=16, nb=need: \
+        L.paged_decode_attn_fp8kv(q, k, v, t, l, 1.0, ks, vs, o, ctypes.byref(shape), ws, nb, None)
+    for ks, vs in ((0.0, 1.0), (1.0, -2.0), (float("nan"), 1.0), (1.0, float("inf"))):
+        assert f(ks=ks, vs=vs) == pkv.PKV_ERR_SHAPE
+    assert f(shape=pkv.make_shape(4, 8, 2, 19, 128, head_dim=64)) == pkv.PKV_ERR_SHAPE   # 8-bit pools: D = 128 only
+    assert f(shape=pkv.make_shape(4, 8, 2, 19, 128, head_dim=256)) == pkv.PKV_ERR_SHAPE
+    assert f(k=None) == pkv.PKV_ERR_NULL and f(t=None) == pkv.PKV_ERR_NULL
+    assert f(v=24) == pkv.PKV_ERR_ALIGN and f(l=18) == pkv.PKV_ERR_ALIGN
+    assert f(nb=need - 1) == pkv.PKV_ERR_WORKSPACE and f(ws=None) == pkv.PKV_ERR_WORKSPACE
+    sh0 = pkv.make_shape(0, 8, 2, 19, 128)
+    assert f(q=None, k=None, v=None, t=None, l=None, o=None, shape=sh0, ws=None, nb=0) == pkv.PKV_OK
+    g = lambda kn=16, vn=16, k=16, v=16, t=16, l=16, ks=0.01, vs=0.02, shape=sh: \
+        L.kv_append_fp8(kn, vn, k, v, t, l, ks, vs, ctypes.byref(shape), None)
+    assert g(ks=0.0) == pkv.PKV_ERR_SHAPE and g(vs=float("nan")) == pkv.PKV_ERR_SHAPE
+    assert g(shape=pkv.make_shape(4, 8, 2, 19, 128, head_dim=64)) == pkv.PKV_ERR_SHAPE
+    assert g(kn=None) == pkv.PKV_ERR_NULL and g(v=None) == pkv.PKV_ERR_NULL
+    assert g(vn=24) == pkv.PKV_ERR_ALIGN and g(t=18) == pkv.PKV_ERR_ALIGN
+    assert g(kn=None, vn=None, k=None, v=None, t=None, l=None, shape=sh0) == pkv.PKV_OK
+
+
+def test_static_call_and_fault_counter_argument_errors():
+    L = pkv.lib()
+    sh = pkv.make_shape(4, 8, 2, 19, 128)
+    f = lambda q=16, k=16, v=16, t=16, l=16, o=16, shape=sh: \
+        L.paged_decode_attn_static(q, k, v, t, l, 1.0, o, ctypes.byref(shape), None)
+    assert f(shape=pkv.make_shape(4, 9, 2, 19, 128)) == pkv.PKV_ERR_SHAPE
+    # 2048 requests x 8 KV heads of 16-head records exceed the library's fixed workspace
+    big = pkv.make_shape(2048, 128, 8, 4, 64)
+    assert pkv.pkv_attn_workspace_bytes(big) > pkv.STATIC_WORKSPACE_BYTES
+    assert f(shape=big) == pkv.PKV_ERR_WORKSPACE
+    assert f(q=None) == pkv.PKV_ERR_NULL and f(o=24) == pkv.PKV_ERR_ALIGN
+    sh0 = pkv.make_shape(0, 8, 2, 19, 128)
+    assert f(q=None, k=None, v=None, t=None, l=None, o=None, shape=sh0) == pkv.PKV_OK
+    assert L.pkv_set_id_fault_counter(2) == pkv.PKV_ERR_ALIGN
+    assert L.pkv_set_id_fault_counter(None) == pkv.PKV_OK
