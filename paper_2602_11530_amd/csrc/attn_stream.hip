@@ -45,9 +45,9 @@
 // reads a lane of those registers per block, so no memory access sits on the
 // address path of the KV loads.
 //
-// Memory traffic.  The eight 16-byte KV loads of a block are nontemporal and
-// unconditional; a ring of kRing register buffers keeps kRing - 1 blocks in
-// flight per wavefront.  Finished records are parked in LDS and written in
+// Memory traffic.  The KV loads of a block (eight of 16 bytes at D = 128) are
+// nontemporal and unconditional; a ring of kRing register buffers keeps
+// kRing - 1 blocks in flight per wavefront.  Finished records are parked in LDS and written in
 // bursts of full-width write-through stores that the compiler's wait-count
 // bookkeeping does not see (see store_record16).
 #include "pkv_kernels.h"
@@ -121,7 +121,8 @@ __device__ __forceinline__ u32x2 widen_e4m3x4(uint32_t w) {
 // (loads retire in order among themselves, so extra pending stores only make the
 // same wait stricter), and the record itself is only read by the next kernel.
 // sc1 makes the store write through instead of leaving a dirty line behind for a
-// later eviction: with it a partition of 512 tokens costs 8 % instead of 13 %.
+// later eviction (measured while records were still written once per partition:
+// 512-token partitions then cost 8 % instead of 13 % on the long-context batch).
 __device__ __forceinline__ void store_record16(float* p, f32x4 v) {
   // the trailing s_nop covers the wait states a wide store needs before a vector
   // op may overwrite its data registers (the compiler cannot see that this is a store)
@@ -130,7 +131,7 @@ __device__ __forceinline__ void store_record16(float* p, f32x4 v) {
 
 // One window of block descriptors: lane i describes stream index jbase + i.
 struct Window {
-  int slab;   // which 4 KiB slab (16 tokens of one KV head), in slabs from the pool's start; 0 when not read
+  int slab;   // which slab (16 tokens of one KV head; 4 KiB at D = 128 in bf16), counted from the pool's start; 0 when not read
   int meta;   // bits 0-7 valid tokens (0..16), bit 8 closes a run, bit 9 first block of a segment here
   int qrow;   // s * Hq + kvh * G: first query/output row of the segment
   int slot;   // partial-record slot of the run this block belongs to
