@@ -128,9 +128,11 @@ def record_traffic(args):
     digest = kernel_sources_digest()
     if rec.get("kernel_sources_sha256") != digest:
         rec = {"kernel_sources_sha256": digest, "workloads": {}}
-    try:
-        rec["commit"] = subprocess.check_output(["git", "-C", ROOT, "rev-parse", "--short", "HEAD"],
-                                                text=True).strip()
+    try:   # the commit whose tree holds the measured kernel sources: HEAD, unless they are modified
+        dirty = subprocess.run(["git", "-C", ROOT, "diff", "--quiet", "HEAD", "--"] +
+                               [os.path.join("paper_2602_11530_amd", "csrc", n) for n in KERNEL_SOURCES]).returncode
+        head = subprocess.check_output(["git", "-C", ROOT, "rev-parse", "--short", "HEAD"], text=True).strip()
+        rec["commit"] = head + (" + uncommitted changes to the kernel sources" if dirty else "")
     except (OSError, subprocess.CalledProcessError):
         rec["commit"] = None
     rec["note"] = ("rocprofv3 --pmc FETCH_SIZE and --pmc WRITE_SIZE (KiB per dispatch), averaged over the "
