@@ -21,8 +21,9 @@ thread_local int32_t* g_id_faults = nullptr;   // see pkv_set_id_fault_counter
 inline bool misaligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) != 0; }
 
 // Library's partition choice when the caller leaves it open.  With the stream
-// decomposition a partition only bounds how many tokens one partial record may
-// stand for, so a large value costs nothing but the record it closes.
+// decomposition a partition only bounds how many tokens one partial result may
+// stand for before it is folded into its segment's record, so the largest value
+// is the cheapest.
 constexpr int kDefaultPartition = pkv::kMaxPartition;
 
 struct Geometry {
@@ -54,7 +55,7 @@ int check_shape(const pkv_attn_shape* sh, Geometry* g) {
   if (P % B != 0 || P < B || P > pkv::kMaxPartition) return PKV_ERR_SHAPE;
   // 4 KiB slabs (16 tokens of one KV head) are numbered in 32 bits on the device
   if (sh->num_pool_blocks < 1 ||
-      sh->num_pool_blocks * sh->num_kv_heads * (B / pkv::kBlockTokens) > INT32_MAX)
+      sh->num_pool_blocks > INT32_MAX / ((int64_t)sh->num_kv_heads * (B / pkv::kBlockTokens)))
     return PKV_ERR_SHAPE;
   // stream positions, slots and rows are 32-bit on the device
   const int64_t max_blocks = (max_ctx + pkv::kBlockTokens - 1) / pkv::kBlockTokens;
@@ -116,7 +117,7 @@ int static_scratch(void** out) {
 
 extern "C" {
 
-int pkv_version(void) { return 1000; }
+int pkv_version(void) { return 1001; }
 
 const char* pkv_status_string(int status) {
   switch (status) {

@@ -41,6 +41,10 @@ int main(void) {
     EXPECT(pkv_attn_workspace_bytes(&s, &bytes) == PKV_OK || pkv_attn_workspace_bytes(&s, &bytes) == PKV_ERR_SHAPE, 1);
     s.max_blocks_per_seq = INT32_MAX;
     EXPECT(pkv_attn_workspace_bytes(&s, &bytes), PKV_ERR_SHAPE);
+    s = ok; s.num_pool_blocks = INT64_MAX;                 /* the slab count must not be formed by a product */
+    EXPECT(pkv_attn_workspace_bytes(&s, &bytes), PKV_ERR_SHAPE);
+    s = ok; s.num_pool_blocks = INT64_MAX / 2; s.num_kv_heads = 8; s.num_q_heads = 8; s.block_size = 64; s.partition_size = 64;
+    EXPECT(pkv_attn_workspace_bytes(&s, &bytes), PKV_ERR_SHAPE);
     s = ok; s.head_dim = 256; s.num_q_heads = 32;
     EXPECT(pkv_attn_workspace_bytes(&s, &bytes), PKV_ERR_SHAPE);
     s = ok; s.partition_size = -16;
