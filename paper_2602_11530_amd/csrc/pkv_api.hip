@@ -26,6 +26,8 @@ inline bool misaligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p)
 // is the cheapest.
 constexpr int kDefaultPartition = pkv::kMaxPartition;
 
+constexpr int kMaxHeads = 65536;   // query heads; keeps every size product far inside 64 bits
+
 struct Geometry {
   int G, P, max_ctx;
   int64_t slots;   // upper bound on partial-record slots
@@ -34,7 +36,8 @@ struct Geometry {
 int check_shape(const pkv_attn_shape* sh, Geometry* g) {
   if (!sh) return PKV_ERR_NULL;
   if (sh->num_seqs < 0 || sh->num_seqs > pkv::kMaxSeqs) return PKV_ERR_SHAPE;
-  if (sh->num_q_heads <= 0 || sh->num_kv_heads <= 0) return PKV_ERR_SHAPE;
+  if (sh->num_q_heads <= 0 || sh->num_kv_heads <= 0 || sh->num_q_heads > kMaxHeads)
+    return PKV_ERR_SHAPE;
   const int D = sh->head_dim;
   if (D != 64 && D != 128 && D != 256) return PKV_ERR_SHAPE;
   const int B = sh->block_size;

@@ -45,6 +45,8 @@ int main(void) {
     EXPECT(pkv_attn_workspace_bytes(&s, &bytes), PKV_ERR_SHAPE);
     s = ok; s.num_pool_blocks = INT64_MAX / 2; s.num_kv_heads = 8; s.num_q_heads = 8; s.block_size = 64; s.partition_size = 64;
     EXPECT(pkv_attn_workspace_bytes(&s, &bytes), PKV_ERR_SHAPE);
+    s = ok; s.num_q_heads = INT32_MAX; s.num_kv_heads = INT32_MAX; s.num_seqs = 2048; s.max_blocks_per_seq = INT32_MAX / 16;
+    EXPECT(pkv_attn_workspace_bytes(&s, &bytes), PKV_ERR_SHAPE);
     s = ok; s.head_dim = 256; s.num_q_heads = 32;
     EXPECT(pkv_attn_workspace_bytes(&s, &bytes), PKV_ERR_SHAPE);
     s = ok; s.partition_size = -16;
