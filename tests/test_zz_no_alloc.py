@@ -64,3 +64,60 @@ def test_static_workspace_limit_is_enforced(device):
     with pytest.raises(pkv.PkvError) as e:
         pkv.paged_decode_attn_static(t, t, t, t, t, 1.0, t, shape)
     assert e.value.status == pkv.PKV_ERR_WORKSPACE
+
+
+def test_static_workspace_call_under_graph_capture(device):
+    """The callers this entry point is for: a decode step (append + attention) recorded into a HIP
+    graph with no workspace to carry around, replayed for four steps with growing lengths and fresh
+    inputs; every replay equals the same step run eagerly with a caller-owned workspace and is
+    within tolerance of the oracle.  The entry point is called once before the capture, as the
+    header asks (its first call on a device looks up the array's address)."""
+    n_steps = 4
+    final = np.array([40, 16 * 9 + 1, 1030, 5, 2300, 64], np.int32)
+    w = wl.custom(final, 40, 8, seed=58, num_pool_blocks=330)
+    rng = np.random.default_rng(58)
+    _, k_h, v_h = wl.make_host_tensors(w)
+    k_g, v_g = to_dev(k_h), to_dev(v_h)
+    k_e, v_e = k_g.clone(), v_g.clone()
+    t_d = to_dev(w.block_tables)
+    shape = shape_of(w)
+    assert pkv.pkv_attn_workspace_bytes(shape) <= pkv.STATIC_WORKSPACE_BYTES
+    ws = torch.empty(pkv.pkv_attn_workspace_bytes(shape), dtype=torch.uint8, device=device)
+    S, Hkv = w.num_seqs, w.num_kv_heads
+    lens_d = to_dev(final - n_steps)
+    q_s = torch.zeros(w.q_shape(), dtype=torch.int16, device=device)
+    kn_s = torch.zeros((S, Hkv, 128), dtype=torch.int16, device=device)
+    vn_s = torch.zeros((S, Hkv, 128), dtype=torch.int16, device=device)
+    out_s = torch.full(w.q_shape(), 0x7FC1, dtype=torch.int16, device=device)
+    # first call outside the capture
+    pkv.paged_decode_attn_static(q_s, k_g, v_g, t_d, lens_d, float(w.scale), out_s, shape)
+    torch.cuda.synchronize()
+
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        pkv.kv_append(kn_s, vn_s, k_g, v_g, t_d, lens_d, shape)
+        pkv.paged_decode_attn_static(q_s, k_g, v_g, t_d, lens_d, float(w.scale), out_s, shape)
+    torch.cuda.synchronize()
+    assert torch.equal(k_g, k_e), "capture must execute nothing"
+
+    for step in range(n_steps):
+        lens_d.add_(1)
+        w.context_lens = final - n_steps + step + 1
+        assert_launchable(w)
+        q, kn, vn = wl.normal_bf16(rng, w.q_shape()), wl.normal_bf16(rng, (S, Hkv, 128)), \
+            wl.normal_bf16(rng, (S, Hkv, 128))
+        q_s.copy_(to_dev(q)); kn_s.copy_(to_dev(kn)); vn_s.copy_(to_dev(vn))
+        out_s.fill_(0x7FC1)
+        graph.replay()
+        torch.cuda.synchronize()
+        replayed = out_s.clone()
+        eager = torch.full(w.q_shape(), 0x7FC1, dtype=torch.int16, device=device)
+        pkv.kv_append(kn_s, vn_s, k_e, v_e, t_d, lens_d, shape)
+        pkv.paged_decode_attn(q_s, k_e, v_e, t_d, lens_d, float(w.scale), eager, shape, ws)
+        torch.cuda.synchronize()
+        assert torch.equal(replayed, eager), f"step {step}: replay != eager"
+        assert torch.equal(k_g, k_e) and torch.equal(v_g, v_e)
+        k_h, v_h = oracle.kv_append(kn, vn, k_h, v_h, w.block_tables, w.context_lens)
+        ref = oracle.paged_decode_attn(q, k_h, v_h, w.block_tables, w.context_lens, w.scale)
+        c = oracle.compare(to_bits(replayed), ref)
+        assert c["max_abs"] <= MAX_ABS and c["rel_l2"] <= REL_L2, (step, c)
