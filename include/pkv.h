@@ -158,8 +158,8 @@ int paged_decode_attn_layers(const void* const* q, const void* const* k_pools,
  *                   is Hkv * B * D bytes (16 KiB at 8 x 16 x 128); the copies
  *                   (gather, scatter, move, offload, reload) take such a pool as
  *                   it is, with that block_bytes
- *   k_scale,v_scale positive finite fp32
- *   shape           head_dim must be 128 (PKV_ERR_SHAPE otherwise)
+ *   k_scale,v_scale positive finite fp32 (PKV_ERR_SHAPE otherwise)
+ *   shape           as for paged_decode_attn: every head_dim and block_size
  * NaN bytes inside a request's valid rows propagate as NaN; unused slots and
  * unused blocks may hold any bytes.
  */
@@ -303,7 +303,7 @@ int kv_append(const void* k_new, const void* v_new, void* k_pool, void* v_pool,
  *
  *   k_new, v_new  device  bf16 [S][Hkv][D]
  *   k_pool,v_pool device  e4m3 [NB][Hkv][B][D]
- *   k_scale, v_scale  positive finite fp32; head_dim must be 128
+ *   k_scale, v_scale  positive finite fp32 (PKV_ERR_SHAPE otherwise)
  */
 int kv_append_fp8(const void* k_new, const void* v_new, void* k_pool, void* v_pool,
                   const int32_t* block_tables, const int32_t* context_lens, float k_scale,

@@ -72,11 +72,20 @@ template <> struct Dim<256, false> {
   static constexpr int kKSteps = 8, kKLoads = 8, kVLoads = 8, kTiles = 16, kRing = 4, kElemBytes = 2;
   typedef uint32_t VReg __attribute__((ext_vector_type(4)));
 };
-// K and V stored as one-byte e4m3 values (D = 128): a block is half the bytes, so the ring is
-// twice as deep; the values are widened to bf16 (exactly) in registers and then take the same
-// path as a bf16 pool.
+// K and V stored as one-byte e4m3 values: a block is half the bytes, so the ring is twice as
+// deep; the values are widened to bf16 (exactly) in registers and then take the same path as a
+// bf16 pool.  A K load is 16 bytes = 16 dims of one token and feeds two MFMA steps; a V load is
+// the lane's dims of one token (4 bytes at D = 64, 8 bytes otherwise).
+template <> struct Dim<64, true> {
+  static constexpr int kKSteps = 2, kKLoads = 1, kVLoads = 4, kTiles = 4, kRing = 8, kElemBytes = 1;
+  typedef uint32_t VReg;
+};
 template <> struct Dim<128, true> {
   static constexpr int kKSteps = 4, kKLoads = 2, kVLoads = 4, kTiles = 8, kRing = 8, kElemBytes = 1;
+  typedef uint32_t VReg __attribute__((ext_vector_type(2)));
+};
+template <> struct Dim<256, true> {
+  static constexpr int kKSteps = 8, kKLoads = 4, kVLoads = 8, kTiles = 16, kRing = 8, kElemBytes = 1;
   typedef uint32_t VReg __attribute__((ext_vector_type(2)));
 };
 // First dim of output tiles 4t..4t+3 (they are consecutive dims) in the lane of column n.
@@ -296,10 +305,10 @@ __global__ __launch_bounds__(kStreamWavesPerGroup * 64) void attn_stream_kernel(
     const int idx = j - jbase;   // always inside window A
     // The MFMA operands.  bf16 pools: the loaded registers themselves.  e4m3 pools: load L of
     // K holds dims 16*(4L + c) .. +15 of token tau(n), which feed steps 2L and 2L + 1 (the
-    // contraction order is free as long as q follows it, see below); load e of V holds dims
-    // 8n .. 8n+7 of token 4e + c as eight bytes.
+    // contraction order is free as long as q follows it, see below); a V load holds the same
+    // token and dims as in a bf16 pool, one byte each.
     u32x4 k[kKSteps];
-    VOp v[kFp8 ? 4 : kVLoads];
+    VOp v[kVLoads];
     if constexpr (kFp8) {
 #pragma unroll
       for (int jj = 0; jj < kKSteps; ++jj) {
@@ -308,9 +317,13 @@ __global__ __launch_bounds__(kStreamWavesPerGroup * 64) void attn_stream_kernel(
         k[jj] = u32x4{a2.x, a2.y, b2.x, b2.y};
       }
 #pragma unroll
-      for (int e = 0; e < 4; ++e) {
-        const u32x2 a2 = widen_e4m3x4(vraw[e].x), b2 = widen_e4m3x4(vraw[e].y);
-        v[e] = VOp{a2.x, a2.y, b2.x, b2.y};
+      for (int e = 0; e < kVLoads; ++e) {
+        if constexpr (kD == 64) {
+          v[e] = widen_e4m3x4(vraw[e]);
+        } else {
+          const u32x2 a2 = widen_e4m3x4(vraw[e].x), b2 = widen_e4m3x4(vraw[e].y);
+          v[e] = VOp{a2.x, a2.y, b2.x, b2.y};
+        }
       }
     } else {
 #pragma unroll
@@ -504,8 +517,10 @@ hipError_t launch_attn_stream(const AttnLaunch& a_in, hipStream_t stream) {
   const size_t lds = cum_bytes + (size_t)kStreamWavesPerGroup * a.rec_buffered * rec_bytes;
   const dim3 grid(a.waves / kStreamWavesPerGroup), block(kStreamWavesPerGroup * 64);
   if (a.kv_fp8) {
-    if (a.D != 128) return hipErrorInvalidValue;
-    hipLaunchKernelGGL((attn_stream_kernel<128, true>), grid, block, lds, stream, a);
+    if (a.D == 64) hipLaunchKernelGGL((attn_stream_kernel<64, true>), grid, block, lds, stream, a);
+    else if (a.D == 128) hipLaunchKernelGGL((attn_stream_kernel<128, true>), grid, block, lds, stream, a);
+    else if (a.D == 256) hipLaunchKernelGGL((attn_stream_kernel<256, true>), grid, block, lds, stream, a);
+    else return hipErrorInvalidValue;
   } else if (a.D == 64) hipLaunchKernelGGL((attn_stream_kernel<64, false>), grid, block, lds, stream, a);
   else if (a.D == 128) hipLaunchKernelGGL((attn_stream_kernel<128, false>), grid, block, lds, stream, a);
   else if (a.D == 256) hipLaunchKernelGGL((attn_stream_kernel<256, false>), grid, block, lds, stream, a);

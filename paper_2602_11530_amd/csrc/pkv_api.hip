@@ -120,7 +120,7 @@ int static_scratch(void** out) {
 
 extern "C" {
 
-int pkv_version(void) { return 1001; }
+int pkv_version(void) { return 1002; }
 
 const char* pkv_status_string(int status) {
   switch (status) {
@@ -242,7 +242,6 @@ int paged_decode_attn_fp8kv(const void* q, const void* k_pool, const void* v_poo
   Geometry g;
   int rc = check_shape(shape, &g);
   if (rc != PKV_OK) return rc;
-  if (shape->head_dim != 128) return PKV_ERR_SHAPE;   // the one-byte pool layout is built for D = 128
   if (!(k_scale > 0.f) || !(v_scale > 0.f) || !(k_scale < __builtin_inff()) ||
       !(v_scale < __builtin_inff()))
     return PKV_ERR_SHAPE;
@@ -331,7 +330,6 @@ int kv_append_fp8(const void* k_new, const void* v_new, void* k_pool, void* v_po
   Geometry g;
   const int rc = check_shape(shape, &g);
   if (rc != PKV_OK) return rc;
-  if (shape->head_dim != 128) return PKV_ERR_SHAPE;
   if (!(k_scale > 0.f) || !(v_scale > 0.f) || !(k_scale < __builtin_inff()) ||
       !(v_scale < __builtin_inff()))
     return PKV_ERR_SHAPE;

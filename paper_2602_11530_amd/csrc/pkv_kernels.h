@@ -65,7 +65,7 @@ struct AttnLaunch {
   int32_t* ws_cum; // [S + 1] cumB, written by the stream pass for the merge
   float scale_log2e;   // softmax scale x log2(e) (x the K pool's scale for an e4m3 pool)
   float out_scale;     // applied to the normalised row: 1, or the V pool's scale
-  int kv_fp8;          // the pools hold one-byte e4m3 values (D = 128 only)
+  int kv_fp8;          // the pools hold one-byte e4m3 values
   int32_t* id_faults;  // optional device counter of refused block ids (nullptr: not reported)
   int S, Hq, Hkv, G, MAXB;
   int D;           // head dimension: 64, 128 or 256

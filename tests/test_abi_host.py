@@ -224,8 +224,8 @@ def test_fp8kv_argument_errors_before_launch():
         L.paged_decode_attn_fp8kv(q, k, v, t, l, 1.0, ks, vs, o, ctypes.byref(shape), ws, nb, None)
     for ks, vs in ((0.0, 1.0), (1.0, -2.0), (float("nan"), 1.0), (1.0, float("inf"))):
         assert f(ks=ks, vs=vs) == pkv.PKV_ERR_SHAPE
-    assert f(shape=pkv.make_shape(4, 8, 2, 19, 128, head_dim=64)) == pkv.PKV_ERR_SHAPE   # 8-bit pools: D = 128 only
-    assert f(shape=pkv.make_shape(4, 8, 2, 19, 128, head_dim=256)) == pkv.PKV_ERR_SHAPE
+    assert f(shape=pkv.make_shape(4, 8, 2, 19, 128, head_dim=96)) == pkv.PKV_ERR_SHAPE
+    assert f(shape=pkv.make_shape(4, 32, 2, 19, 128, head_dim=256)) == pkv.PKV_ERR_SHAPE   # G = 16 at D = 256
     assert f(k=None) == pkv.PKV_ERR_NULL and f(t=None) == pkv.PKV_ERR_NULL
     assert f(v=24) == pkv.PKV_ERR_ALIGN and f(l=18) == pkv.PKV_ERR_ALIGN
     assert f(nb=need - 1) == pkv.PKV_ERR_WORKSPACE and f(ws=None) == pkv.PKV_ERR_WORKSPACE
@@ -234,7 +234,7 @@ def test_fp8kv_argument_errors_before_launch():
     g = lambda kn=16, vn=16, k=16, v=16, t=16, l=16, ks=0.01, vs=0.02, shape=sh: \
         L.kv_append_fp8(kn, vn, k, v, t, l, ks, vs, ctypes.byref(shape), None)
     assert g(ks=0.0) == pkv.PKV_ERR_SHAPE and g(vs=float("nan")) == pkv.PKV_ERR_SHAPE
-    assert g(shape=pkv.make_shape(4, 8, 2, 19, 128, head_dim=64)) == pkv.PKV_ERR_SHAPE
+    assert g(shape=pkv.make_shape(4, 8, 2, 19, 128, head_dim=96)) == pkv.PKV_ERR_SHAPE
     assert g(kn=None) == pkv.PKV_ERR_NULL and g(v=None) == pkv.PKV_ERR_NULL
     assert g(vn=24) == pkv.PKV_ERR_ALIGN and g(t=18) == pkv.PKV_ERR_ALIGN
     assert g(kn=None, vn=None, k=None, v=None, t=None, l=None, shape=sh0) == pkv.PKV_OK

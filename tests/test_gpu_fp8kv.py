@@ -42,19 +42,22 @@ def check(w, q, k8, v8, got, what, k_scale=KS, v_scale=VS):
     assert abs_error_within_bar(got, ref), c
 
 
-def test_every_byte_decodes_as_e4m3(device):
+@pytest.mark.parametrize("D", [64, 128, 256])
+def test_every_byte_decodes_as_e4m3(device, D):
     """A one-token context returns v_scale * (its V row) exactly: rows holding all 254 finite bytes
-    show that the device reads the bytes as OCP E4M3 (bias 7, subnormals, +-448), bit for bit."""
-    w = wl.custom([1, 1], 2, 2, seed=3, num_pool_blocks=4)
+    show that the device reads the bytes as OCP E4M3 (bias 7, subnormals, +-448), bit for bit, and
+    that every lane's bytes of a V row land in the right output dim at every head dimension."""
+    H = 256 // D
+    w = wl.custom([1, 1], H, H, seed=3, num_pool_blocks=4, head_dim=D)
     q, k8, v8 = wl.make_host_tensors_fp8(w, KS, VS)
     codes = np.arange(256, dtype=np.uint8)
     codes[[0x7F, 0xFF]] = 0
     for s in range(2):
-        v8[w.block_tables[s, 0], :, 0, :] = codes.reshape(2, 128) if s == 0 else codes[::-1].reshape(2, 128)
+        v8[w.block_tables[s, 0], :, 0, :] = codes.reshape(H, D) if s == 0 else codes[::-1].reshape(H, D)
     for v_scale in (1.0, 0.5, 4.0):          # powers of two keep the product exact in bf16
         got = wl.bf16_bits_to_f64(run_fp8(w, q, k8, v8, v_scale=v_scale)).reshape(w.q_shape())
         want = np.array([[v_scale * oracle.e4m3(b) for b in v8[w.block_tables[s, 0], h, 0]]
-                         for s in range(2) for h in range(2)]).reshape(w.q_shape())
+                         for s in range(2) for h in range(H)]).reshape(w.q_shape())
         assert np.array_equal(got, want)
 
 
@@ -68,6 +71,38 @@ def test_edge_lengths(device, B, P):
         got = run_fp8(w, q, k8, v8)
         check(w, q, k8, v8, got, f"fp8 B={B} hq={hq} hkv={hkv} P={P}")
         assert not got.reshape(w.q_shape())[EDGE.index(0)].any()
+
+
+@pytest.mark.parametrize("D", [64, 256])
+@pytest.mark.parametrize("P", [0, 64, 512])
+def test_edge_lengths_other_head_dims(device, D, P):
+    for B, hq, hkv in [(16, 40, 8), (32, 8, 2), (64, 7, 7), (16, 16 if D == 64 else 8, 1)]:
+        w = wl.custom(EDGE, hq, hkv, seed=950 + B + hq + D, num_pool_blocks=300, partition_size=P,
+                      block_size=B, head_dim=D)
+        q, k8, v8 = wl.make_host_tensors_fp8(w, KS, VS, poison_unused=True)
+        print(f"fp8 D={D} B={B} P={P} hq={hq} hkv={hkv}", flush=True)
+        got = run_fp8(w, q, k8, v8)
+        check(w, q, k8, v8, got, f"fp8 D={D} B={B} hq={hq} hkv={hkv} P={P}")
+        assert not got.reshape(w.q_shape())[EDGE.index(0)].any()
+
+
+@pytest.mark.parametrize("D", [64, 256])
+def test_invariances_other_head_dims(device, D):
+    """Physical block permutation is bitwise, the partition size stays within tolerance."""
+    lens = [1300, 77, 2048, 640, 33, 4100]
+    w = wl.custom(lens, 40, 8, seed=6, head_dim=D)
+    q, k8, v8 = wl.make_host_tensors_fp8(w, KS, VS)
+    base = run_fp8(w, q, k8, v8)
+    perm = np.random.default_rng(10).permutation(w.num_pool_blocks).astype(np.int32)
+    k2, v2 = np.empty_like(k8), np.empty_like(v8)
+    k2[perm], v2[perm] = k8, v8
+    tables2 = np.where(w.block_tables >= 0, perm[np.maximum(w.block_tables, 0)], -1).astype(np.int32)
+    w2 = wl.Workload("perm", 40, 8, w.context_lens, tables2, w.num_pool_blocks, seed=w.seed, head_dim=D)
+    assert np.array_equal(run_fp8(w2, q, k2, v2), base)
+    ref = oracle.paged_decode_attn_fp8kv(q, k8, v8, w.block_tables, w.context_lens, w.scale, KS, VS)
+    for P in (16, 512, 4096):
+        c = oracle.compare(run_fp8(w, q, k8, v8, partition_size=P), ref)
+        assert c["max_abs"] <= MAX_ABS and c["rel_l2"] <= REL_L2, (D, P, c)
 
 
 def test_invariances(device):
@@ -130,16 +165,17 @@ def test_argument_errors(device):
         with pytest.raises(pkv.PkvError) as e:
             pkv.paged_decode_attn_fp8kv(*args, 0.1, ks, vs, out, shape, ws)
         assert e.value.status == pkv.PKV_ERR_SHAPE
-    shape64 = pkv.make_shape(2, 8, 2, w.max_blocks_per_seq, 8, head_dim=64)
+    shape96 = pkv.make_shape(2, 8, 2, w.max_blocks_per_seq, 8, head_dim=96)
     with pytest.raises(pkv.PkvError) as e:
-        pkv.paged_decode_attn_fp8kv(*args, 0.1, 1.0, 1.0, out, shape64, ws)
+        pkv.paged_decode_attn_fp8kv(*args, 0.1, 1.0, 1.0, out, shape96, ws)
     assert e.value.status == pkv.PKV_ERR_SHAPE
 
 
-def test_config2_in_8_bits(device):
+@pytest.mark.parametrize("D", [128, 64, 256])
+def test_config2_in_8_bits(device, D):
     """The Qwen-32B-shaped batch with E4M3 pools: full oracle parity, and the rate it streams at
-    (half the KV bytes of the bf16 batch)."""
-    w = wl.cfg2_qwen32b()
+    (half the KV bytes of the bf16 batch), at every head dimension."""
+    w = wl.cfg2_qwen32b(head_dim=D)
     assert_launchable(w)
     g = torch.Generator(device=device)
     g.manual_seed(w.seed + 19)
@@ -165,27 +201,31 @@ def test_config2_in_8_bits(device):
     torch.cuda.synchronize()
     ms = a.elapsed_time(b) / reps
     nbytes = w.attn_algorithmic_bytes() - w.total_tokens * w.num_kv_heads * w.head_dim * 2   # KV at 1 B
-    print(f"\nfp8 KV: {nbytes / 1e9:.3f} GB in {ms:.4f} ms = {nbytes / ms / 1e6:.0f} GB/s, "
+    print(f"\nfp8 KV D={D}: {nbytes / 1e9:.3f} GB in {ms:.4f} ms = {nbytes / ms / 1e6:.0f} GB/s, "
           f"{w.total_tokens / ms / 1e6:.3f} G tokens attended/s", flush=True)
-    check(w, to_bits(q), k8.cpu().numpy(), v8.cpu().numpy(), to_bits(out), "cfg2 with E4M3 pools")
+    check(w, to_bits(q), k8.cpu().numpy(), v8.cpu().numpy(), to_bits(out), f"cfg2 with E4M3 pools, D={D}")
 
 
-def test_append_quantises_bit_exactly(device):
+@pytest.mark.parametrize("D", [128, 64, 256])
+def test_append_quantises_bit_exactly(device, D):
     """kv_append_fp8 equals the oracle byte for byte: ordinary rows, rows that saturate, values on
     and next to the rounding boundaries of the format, zeros of both signs."""
-    w = wl.custom([1, 16, 17, 0, 300, 33, 512, 513], 40, 8, seed=41, num_pool_blocks=120)
+    w = wl.custom([1, 16, 17, 0, 300, 33, 512, 513], 40, 8, seed=41, num_pool_blocks=120, head_dim=D)
     rng = np.random.default_rng(8)
     _, k8, v8 = wl.make_host_tensors_fp8(w, KS, VS)
-    k_new, v_new = wl.normal_bf16(rng, (w.num_seqs, 8, 128)), wl.normal_bf16(rng, (w.num_seqs, 8, 128))
-    # midpoints between neighbouring E4M3 values (times the scale) and their bf16 neighbours
+    k_new, v_new = wl.normal_bf16(rng, (w.num_seqs, 8, D)), wl.normal_bf16(rng, (w.num_seqs, 8, D))
+    # midpoints between neighbouring E4M3 values (times the scale) and their bf16 neighbours,
+    # 120 of them laid over as many (request, head) rows as the head dimension needs
     grid = np.array(sorted({oracle.e4m3(b) for b in range(0x7F)}))
     mids = ((grid[1:] + grid[:-1]) / 2)[:120]
-    for s, scale, new in ((1, float(KS), k_new), (2, float(VS), v_new)):
+    for s0, scale, new in ((1, float(KS), k_new), (4, float(VS), v_new)):
         vals = wl.f32_to_bf16_bits((mids * scale).astype(np.float32))
-        new[s, 0, :120] = vals
-        new[s, 1, :120] = vals + np.uint16(1)
-        new[s, 2, :120] = vals - np.uint16(1)
-        new[s, 3, :8] = wl.f32_to_bf16_bits(np.float32([100.0, -100.0, 0.0, -0.0, 6.5, -6.5, 1e-6, 448 * scale]))
+        for i0 in range(0, 120, D):
+            part, s = vals[i0:i0 + D], s0 + i0 // D
+            new[s, 0, :len(part)] = part
+            new[s, 1, :len(part)] = part + np.uint16(1)
+            new[s, 2, :len(part)] = part - np.uint16(1)
+        new[s0, 3, :8] = wl.f32_to_bf16_bits(np.float32([100.0, -100.0, 0.0, -0.0, 6.5, -6.5, 1e-6, 448 * scale]))
     k_d, v_d = dev8(k8), dev8(v8)
     pkv.kv_append_fp8(to_dev(k_new), to_dev(v_new), k_d, v_d, to_dev(w.block_tables),
                       to_dev(w.context_lens), float(KS), float(VS), shape_of(w))
@@ -196,11 +236,12 @@ def test_append_quantises_bit_exactly(device):
     assert (wk != k8).sum() > 1000      # the call did write rows
 
 
-def test_decode_loop_append_then_attend(device):
+@pytest.mark.parametrize("D", [128, 64, 256])
+def test_decode_loop_append_then_attend(device, D):
     """Three decode steps on 8-bit pools: the new rows are quantised and appended by the library,
     attention is checked against the oracle run on pools the oracle appended to itself."""
     final = np.array([20, 48, 515, 1300, 3], np.int32)
-    w = wl.custom(final, 40, 8, seed=77, num_pool_blocks=160)
+    w = wl.custom(final, 40, 8, seed=77, num_pool_blocks=160, head_dim=D)
     rng = np.random.default_rng(5)
     _, k8, v8 = wl.make_host_tensors_fp8(w, KS, VS)
     k_d, v_d, t_d = dev8(k8), dev8(v8), to_dev(w.block_tables)
@@ -210,7 +251,7 @@ def test_decode_loop_append_then_attend(device):
     for back in (2, 1, 0):
         w.context_lens = final - back
         assert_launchable(w)
-        k_new, v_new = wl.normal_bf16(rng, (w.num_seqs, 8, 128)), wl.normal_bf16(rng, (w.num_seqs, 8, 128))
+        k_new, v_new = wl.normal_bf16(rng, (w.num_seqs, 8, D)), wl.normal_bf16(rng, (w.num_seqs, 8, D))
         q = wl.normal_bf16(rng, w.q_shape())
         lens_d = to_dev(w.context_lens)
         out = torch.full(w.q_shape(), 0x7FC1, dtype=torch.int16, device="cuda:0")
