@@ -55,6 +55,9 @@ def parse():
     ap.add_argument("--kv-dtype", default="bf16", choices=["bf16", "fp8"],
                     help="fp8: the same batch with one-byte E4M3 KV pools (cfg2/cfg3; a workload of its "
                          "own, reported as such)")
+    ap.add_argument("--head-dim", type=int, default=128, choices=[64, 128, 256],
+                    help="cfg2 only: the same batch at another head dimension (a workload of its own, "
+                         "named ..._d64 / ..._d256)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-cfg3", action="store_true", help="default run: skip the long-context sub-record")
     ap.add_argument("--no-migration", action="store_true",
@@ -240,8 +243,8 @@ def single_layer(args, w, dev, steps, warmup, cpu_baseline):
     out = torch.empty(w.q_shape(), dtype=torch.bfloat16, device=dev)
     max_ctx = int(w.context_lens.max())
     shape = pkv.make_shape(w.num_seqs, w.num_q_heads, w.num_kv_heads, w.max_blocks_per_seq,
-                           w.num_pool_blocks, partition_size=w.partition_size,
-                           max_context_len=max_ctx)
+                           w.num_pool_blocks, head_dim=w.head_dim, block_size=w.block_size,
+                           partition_size=w.partition_size, max_context_len=max_ctx)
     P = pkv.pkv_attn_partition_size(shape)
     ws_bytes = pkv.pkv_attn_workspace_bytes(shape)
     ws = torch.empty(max(ws_bytes, 16), dtype=torch.uint8, device=dev)
@@ -566,7 +569,11 @@ def main():
         return full_depth(args, dev)
     if args.workload == "cfg5":
         return migration_next_to_decode(args, dev)
-    w = {"cfg1": wl.cfg1_tiny, "cfg2": wl.cfg2_qwen32b, "cfg3": wl.cfg3_long_cot}[args.workload]()
+    if args.head_dim != 128 and args.workload != "cfg2":
+        print("bench.py: --head-dim applies to --workload cfg2 only", file=sys.stderr)
+        sys.exit(2)
+    w = {"cfg1": wl.cfg1_tiny, "cfg2": lambda: wl.cfg2_qwen32b(head_dim=args.head_dim),
+         "cfg3": wl.cfg3_long_cot}[args.workload]()
     if args.partition is not None:
         w.partition_size = args.partition
     r = single_layer(args, w, dev, args.steps, args.warmup, not args.no_cpu_baseline)
@@ -585,7 +592,8 @@ def main():
     }
     ok = r.get("parity", {}).get("within_bar", True)
 
-    if args.workload == "cfg2" and not args.no_cfg3 and args.partition is None and args.kv_dtype == "bf16":
+    if args.workload == "cfg2" and not args.no_cfg3 and args.partition is None and args.kv_dtype == "bf16" \
+            and args.head_dim == 128:
         # The long-context batch as specified (512-token partitions), in the same line.  It is
         # measured by a child process running this script with --workload cfg3, i.e. exactly as a
         # stand-alone run measures it: in a fresh address space (pools allocated after another
