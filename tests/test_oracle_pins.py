@@ -209,6 +209,45 @@ def test_score_shift_invariance():
     assert np.abs(a).max() > 1e-3
 
 
+def test_split_context_merges_to_the_single_pass():
+    """The split-K identity the GPU path relies on: cut a request's context at block boundaries
+    into pieces, let the checker attend over each piece as a request of its own, and merge the
+    normalised pieces with weights e^(m_p - M) Z_p (maximum and sum of each piece's scores from a
+    dense numpy computation): the merged row equals the checker's single pass over the whole
+    context.  A piece may also be empty (weight 0)."""
+    lens = [300, 1000, 48]
+    w = wl.custom(lens, 8, 2, seed=71)
+    q, k, v = wl.make_host_tensors(w)
+    whole = run(w, q, k, v)
+    G, B = w.num_q_heads // w.num_kv_heads, w.block_size
+    qf = wl.bf16_bits_to_f64(q).reshape(w.q_shape())
+    for cuts in ([128], [16, 32, 512], [48], [0]):
+        for s, L in enumerate(lens):
+            edges = [0] + [c for c in cuts if c < L] + [L]
+            K = depage(w, k, s)
+            num = np.zeros((w.num_q_heads, w.head_dim))
+            den = np.zeros(w.num_q_heads)
+            stats = []
+            for a0, a1 in zip(edges[:-1], edges[1:]):
+                # the piece [a0, a1) as a request: its table row starts at block a0 / B
+                t = np.full((1, w.max_blocks_per_seq), -1, np.int32)
+                nb = (a1 - a0 + B - 1) // B
+                t[0, :nb] = w.block_tables[s, a0 // B:a0 // B + nb]
+                piece = oracle.paged_decode_attn(q[s:s + 1], k, v, t, np.array([a1 - a0], np.int32), w.scale)[0]
+                x = float(np.float32(w.scale)) * np.einsum("tkd,kgd->kgt", K[a0:a1],
+                                                           qf[s].reshape(w.num_kv_heads, G, -1))
+                x = x.reshape(w.num_q_heads, a1 - a0)
+                m = x.max(axis=1) if a1 > a0 else np.full(w.num_q_heads, -np.inf)
+                Z = np.exp(x - m[:, None]).sum(axis=1) if a1 > a0 else np.zeros(w.num_q_heads)
+                stats.append((m, Z, piece))
+            M = np.max([m for m, _, _ in stats], axis=0)
+            for m, Z, piece in stats:
+                wgt = np.where(np.isneginf(m), 0.0, np.exp(m - M)) * Z
+                num += wgt[:, None] * piece
+                den += wgt
+            assert np.abs(num / den[:, None] - whole[s]).max() < 1e-12, (cuts, s)
+
+
 def test_paging_invariance():
     """Permute the physical blocks and rewrite the tables: identical result."""
     w = wl.cfg1_tiny()
