@@ -91,6 +91,11 @@ int pkv_attn_workspace_bytes(const pkv_attn_shape* shape /* host */, size_t* out
  * range (the tokens of such a block are left out of the softmax, so a
  * corrupt table gives a wrong row, not a memory fault), and a negative
  * context_lens[s] counts as 0.  Several requests may map the same block.
+ * NaN or Inf inside the rows a request does attend over propagates as in IEEE
+ * arithmetic and stays where it belongs: a NaN in a K row turns the rows of
+ * that KV head's query group into NaN, a NaN V element turns that output
+ * element into NaN, an infinite V element leaves it non-finite (NaN or Inf);
+ * every other output element is unaffected.
  *
  * Arithmetic: bf16 inputs, fp32 scores, softmax statistics and accumulation,
  * one round-to-nearest-even to bf16 at the end.  The result does not depend on

@@ -307,3 +307,38 @@ def test_length_bound_clamps_and_negative_length_is_empty(device):
     clamped.block_tables = w.block_tables
     check(clamped, q, k, v, got, "clamped to 128, negative length")
     assert not got.reshape(w.q_shape())[3].any()
+
+
+def test_non_finite_values_in_valid_rows_stay_local(device):
+    """NaN or Inf inside the rows a request does attend over propagates the way IEEE arithmetic
+    has it and touches nothing else: a NaN in a K row makes the rows of that KV head's query
+    group NaN in every dim, a NaN in one V element makes exactly that output dim NaN, an infinite
+    V element leaves that dim non-finite; every other output element keeps its bits, and the NaN
+    positions are the checker's."""
+    lens = [300, 1000, 77, 2100]
+    w = wl.custom(lens, 40, 8, seed=83, partition_size=256)
+    q, k, v = wl.make_host_tensors(w)
+    clean = run_attn(w, q, k, v).reshape(w.q_shape())
+    G, B = 5, w.block_size
+    NAN, INF = np.uint16(0x7FC0), np.uint16(0x7F80)
+    k2, v2 = k.copy(), v.copy()
+    where = lambda s, t: (w.block_tables[s, t // B], t % B)
+    blk, slot = where(0, 5);    k2[blk, 1, slot, 40] = NAN        # request 0, KV head 1
+    blk, slot = where(1, 700);  v2[blk, 0, slot, 17] = NAN        # request 1, KV head 0, dim 17
+    blk, slot = where(3, 2099); v2[blk, 7, slot, 127] = INF       # request 3, KV head 7, dim 127
+    blk, slot = where(3, 0);    k2[blk, 2, slot, 0] = NAN         # request 3, KV head 2
+    got = run_attn(w, q, k2, v2).reshape(w.q_shape())
+    gf = wl.bf16_bits_to_f64(got).reshape(w.q_shape())
+    expect_nan = np.zeros(w.q_shape(), bool)
+    expect_nan[0, 1 * G:2 * G, :] = True
+    expect_nan[1, 0:G, 17] = True
+    expect_nan[3, 2 * G:3 * G, :] = True
+    inf_spot = np.zeros(w.q_shape(), bool)
+    inf_spot[3, 7 * G:8 * G, 127] = True
+    assert np.isnan(gf[expect_nan]).all()
+    assert not np.isfinite(gf[inf_spot]).any()
+    rest = ~(expect_nan | inf_spot)
+    assert np.array_equal(got[rest], clean[rest])
+    ref = oracle.paged_decode_attn(q, k2, v2, w.block_tables, w.context_lens, w.scale)
+    assert np.array_equal(np.isnan(ref), expect_nan)
+    assert np.isposinf(ref[inf_spot]).all()

@@ -262,3 +262,24 @@ def test_decode_loop_append_then_attend(device, D):
         k_h, v_h = oracle.kv_append_fp8(k_new, v_new, k_h, v_h, w.block_tables, w.context_lens, KS, VS)
         assert np.array_equal(k_d.cpu().numpy(), k_h) and np.array_equal(v_d.cpu().numpy(), v_h)
         check(w, q, k_h, v_h, to_bits(out), f"fp8 append step -{back}")
+
+
+def test_nan_bytes_in_valid_rows_stay_local(device):
+    """The format's NaN bytes inside attended rows: a NaN in a K row makes that KV head's query
+    group NaN in every dim, a NaN V element makes exactly that output dim NaN; everything else
+    keeps its bits, and the NaN positions are the checker's."""
+    w = wl.custom([300, 1000, 77], 40, 8, seed=84, partition_size=256)
+    q, k8, v8 = wl.make_host_tensors_fp8(w, KS, VS)
+    clean = run_fp8(w, q, k8, v8).reshape(w.q_shape())
+    G, B = 5, w.block_size
+    k2, v2 = k8.copy(), v8.copy()
+    k2[w.block_tables[0, 5 // B], 1, 5 % B, 40] = 0x7F
+    v2[w.block_tables[1, 700 // B], 0, 700 % B, 17] = 0xFF
+    got = run_fp8(w, q, k2, v2).reshape(w.q_shape())
+    expect_nan = np.zeros(w.q_shape(), bool)
+    expect_nan[0, G:2 * G, :] = True
+    expect_nan[1, 0:G, 17] = True
+    assert np.array_equal(np.isnan(wl.bf16_bits_to_f64(got).reshape(w.q_shape())), expect_nan)
+    assert np.array_equal(got[~expect_nan], clean[~expect_nan])
+    ref = oracle.paged_decode_attn_fp8kv(q, k2, v2, w.block_tables, w.context_lens, w.scale, KS, VS)
+    assert np.array_equal(np.isnan(ref), expect_nan)
