@@ -100,8 +100,11 @@ hipError_t launch(const void* src, void* dst, const int32_t* ids_a, const int32_
   const int64_t slices = (chunks + kChunksPerGroup - 1) / kChunksPerGroup;
   const int64_t units = n_blocks * slices;
   // one workgroup per slice (the hardware dispatcher balances them better than a
-  // persistent grid did: 5.4 against 5.2-5.3 TB/s); beyond 2^31-1 the kernel strides
-  const dim3 grid((unsigned)(units > 0x7fffffff ? 0x7fffffff : units));
+  // persistent grid did: 5.4 against 5.2-5.3 TB/s); a list of more than kMaxGroups slices
+  // (256 GiB of 32 KiB slices, or very many tiny blocks) is walked with a stride, which
+  // keeps the launch below 2^32 work-items
+  constexpr int64_t kMaxGroups = (int64_t)1 << 23;
+  const dim3 grid((unsigned)(units > kMaxGroups ? kMaxGroups : units));
   const bool cached = kMode != 2 && n_blocks * block_bytes <= kCachedStagingBytes;
   auto kernel = cached ? kv_block_copy_kernel<kMode, true> : kv_block_copy_kernel<kMode, false>;
   hipLaunchKernelGGL(kernel, grid, dim3(kCopyThreads), 0, stream, (const u32x4*)src, (u32x4*)dst,

@@ -65,6 +65,28 @@ def test_odd_block_bytes_and_empty_list(device):
     assert np.array_equal(to_bits(pool_d), pool)
 
 
+def test_list_longer_than_the_grid(device):
+    """More listed slices than the launch has workgroups (2^23): the kernel walks the list with a
+    stride.  9 million blocks of 16 bytes, gathered, scattered and moved in a seeded order."""
+    n = (1 << 23) + 600_001
+    rng = np.random.default_rng(23)
+    pool = rng.integers(0, 65536, size=(n, 8)).astype(np.uint16)
+    ids = rng.permutation(n).astype(np.int32)
+    pool_d = to_dev(pool)
+    st = gather_gpu(pool_d, ids, 16)
+    want = oracle.kv_blocks_gather(pool, ids)
+    assert np.array_equal(to_bits(st).reshape(want.shape), want)
+    new_ids = rng.permutation(n).astype(np.int32)
+    dst = to_dev(np.zeros_like(pool))
+    pkv.kv_blocks_scatter(st, dst, to_dev(new_ids), n, 16, n)
+    torch.cuda.synchronize()
+    assert np.array_equal(to_bits(dst), oracle.kv_blocks_scatter(want, np.zeros_like(pool), new_ids))
+    dst2 = to_dev(np.zeros_like(pool))
+    pkv.kv_blocks_move(pool_d, to_dev(ids), dst2, to_dev(new_ids), n, 16, n, n)
+    torch.cuda.synchronize()
+    assert np.array_equal(to_bits(dst2), to_bits(dst))
+
+
 def test_migration_keeps_attention_bitwise(device):
     """Gather a quarter of the requests, scatter into reshuffled blocks, rewrite
     their tables: every block image and the attention output are unchanged."""
