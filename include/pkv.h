@@ -45,7 +45,7 @@ extern "C" {
  * library start-up. */
 typedef struct {
   int32_t num_seqs;           /* S: requests in this step's batch, 0..2048              */
-  int32_t num_q_heads;        /* Hq, 1..65536                                            */
+  int32_t num_q_heads;        /* Hq, 1..16384                                            */
   int32_t num_kv_heads;       /* Hkv; Hq % Hkv == 0; query heads h*G..h*G+G-1 share
                                  KV head h (G = Hq/Hkv, 1 <= G <= 16)                    */
   int32_t head_dim;           /* D: 64, 128 or 256 (256 only with G <= 8)                */

@@ -26,7 +26,9 @@ inline bool misaligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p)
 // is the cheapest.
 constexpr int kDefaultPartition = pkv::kMaxPartition;
 
-constexpr int kMaxHeads = 65536;   // query heads; keeps every size product far inside 64 bits
+// Query heads.  Keeps every size product far inside 64 bits and the merge launch (one
+// wavefront per (request, head)) below 2^32 work-items at the largest batch.
+constexpr int kMaxHeads = 16384;
 
 struct Geometry {
   int G, P, max_ctx;

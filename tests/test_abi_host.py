@@ -59,7 +59,7 @@ def test_partition_and_workspace():
 
 @pytest.mark.parametrize("kw", [
     dict(head_dim=96), dict(head_dim=32), dict(head_dim=512), dict(head_dim=256, num_q_heads=32), dict(block_size=48), dict(block_size=128), dict(block_size=8),
-    dict(block_size=32, partition_size=16), dict(block_size=64, num_pool_blocks=2 ** 29), dict(num_q_heads=9), dict(num_kv_heads=0),
+    dict(block_size=32, partition_size=16), dict(block_size=64, num_pool_blocks=2 ** 29), dict(num_q_heads=9), dict(num_kv_heads=0), dict(num_q_heads=16384 + 4096, num_kv_heads=4096 + 1024),
     dict(partition_size=24), dict(partition_size=65536 + 16), dict(num_seqs=2049), dict(partition_size=-16),
     dict(max_blocks_per_seq=0), dict(num_seqs=-1), dict(max_context_len=20 * 16),
     dict(max_context_len=-1), dict(num_pool_blocks=0), dict(num_pool_blocks=2 ** 31),
