@@ -136,3 +136,48 @@ def test_config2_lengths_at_this_head_dim(device, D):
     print(f"D={D}: {w.attn_algorithmic_bytes() / 1e9:.3f} GB in {ms:.4f} ms = "
           f"{w.attn_algorithmic_bytes() / ms / 1e6:.0f} GB/s", flush=True)
     check(w, to_bits(q), to_bits(k), to_bits(v), to_bits(out), f"cfg2 lengths at D={D}")
+
+
+@pytest.mark.parametrize("case", range(36))
+def test_random_shapes_all_variants(device, case):
+    """The seeded corner-case batches of the stream decomposition (fewer blocks than wavefronts,
+    empty requests, shares that begin on partition cuts, one long request among short ones) with
+    the head dimension, the pool format and the block size drawn too."""
+    from test_gpu_attn import _random_case
+    rng = np.random.default_rng(31000 + case)
+    lens, hq, hkv, P = _random_case(rng, case)
+    D = int(rng.choice([64, 256]))
+    fp8 = bool(rng.integers(0, 2))
+    B = int(rng.choice([16, 32, 64]))
+    if D == 256 and hq // hkv > 8:
+        hq = 8 * hkv
+    if P and P % B:
+        P = B * (P // B + 1)
+    need = int(((lens + B - 1) // B).sum())
+    w = wl.custom(lens, hq, hkv, seed=3100 + case, partition_size=P, block_size=B, head_dim=D,
+                  num_pool_blocks=need + int(rng.integers(1, 50)))
+    what = f"case {case}: D={D} fp8={fp8} B={B} S={len(lens)} hq={hq} hkv={hkv} P={P} tokens={int(lens.sum())}"
+    print(what, flush=True)
+    if fp8:
+        ks, vs = np.float32(0.0134), np.float32(0.0171)
+        q, k, v = wl.make_host_tensors_fp8(w, ks, vs, poison_unused=True)
+        assert_launchable(w)
+        shape = shape_of(w)
+        ws = torch.empty(max(pkv.pkv_attn_workspace_bytes(shape), 16), dtype=torch.uint8, device=device)
+        out = torch.full(w.q_shape(), 0x7FC1, dtype=torch.int16, device=device)
+        pkv.paged_decode_attn_fp8kv(to_dev(q), torch.from_numpy(k).to(device), torch.from_numpy(v).to(device),
+                                    to_dev(w.block_tables), to_dev(w.context_lens), float(w.scale),
+                                    float(ks), float(vs), out, shape, ws)
+        torch.cuda.synchronize()
+        got = to_bits(out)
+        ref = oracle.paged_decode_attn_fp8kv(q, k, v, w.block_tables, w.context_lens, w.scale, ks, vs)
+    else:
+        q, k, v = wl.make_host_tensors(w, poison_unused=True)
+        got = run_attn(w, q, k, v)
+        ref = oracle.paged_decode_attn(q, k, v, w.block_tables, w.context_lens, w.scale)
+    c = oracle.compare(got, ref)
+    assert np.isfinite(wl.bf16_bits_to_f64(got)).all()
+    assert c["rel_l2"] <= REL_L2 and c["worst_seq_rel_l2"] <= 2 * REL_L2, (what, c)
+    assert abs_error_within_bar(got, ref), (what, c)
+    for s in np.nonzero(lens == 0)[0]:
+        assert not got.reshape(w.q_shape())[s].any()
