@@ -29,12 +29,11 @@
 //         token order 4*e + c is exactly the one the scores came out in, so P
 //         needs no shuffle between the two products.
 //   D = 64:  lane (n, c) owns dims 4n..4n+3; its V loads are 8 bytes wide (four
-//         fully contiguous 512-byte loads), two K steps, four output tiles, and a
-//         ring twice as deep since a block is half as many bytes.
+//         fully contiguous 512-byte loads), two K steps, four output tiles.
 //   D = 256: lane (n, c) owns dims 8n..8n+7 of each 128-dim half; eight K steps,
 //         eight 16-byte V loads (a 256-byte run per token per load), sixteen
-//         output tiles; a block is 16 KiB here, and the registers of a ring of four
-//         leave room for one wavefront per SIMD, so half as many wavefronts stream.
+//         output tiles; a block is 16 KiB here and a wavefront needs more than half
+//         of a SIMD's registers, so one wavefront per SIMD streams (half as many).
 // The running maximum m is only raised when a score exceeds it by more than
 // 2^kLazyLog2; any reference value gives the same softmax, and the bound keeps
 // every weight within fp32/bf16 range.
@@ -47,7 +46,7 @@
 //
 // Memory traffic.  The KV loads of a block (eight of 16 bytes at D = 128) are
 // nontemporal and unconditional; a ring of kRing register buffers keeps
-// kRing - 1 blocks in flight per wavefront.  Finished records are parked in LDS and written in
+// kRing - 1 blocks (one) in flight per wavefront.  Finished records are parked in LDS and written in
 // bursts of full-width write-through stores that the compiler's wait-count
 // bookkeeping does not see (see store_record16).
 #include "pkv_kernels.h"
@@ -57,35 +56,41 @@ namespace {
 
 constexpr int kWindow = 64;       // descriptors per window: one per lane
 
-// What depends on the head dimension.  kRing: 16-token blocks in flight per
-// wavefront plus the one being consumed (a ring of register buffers).
+// Register buffers per wavefront: the block being consumed and the block in
+// flight behind it.  With 2048 wavefronts (1024 at D = 256) that is 16 MB on its
+// way at any time, which keeps the memory system saturated; deeper rings (4 and
+// 8 were measured, at every head dimension and pool format) only lengthen the
+// queues: 0.5 % slower on the Qwen-32B-shaped batches, 2 to 5 % on the variants
+// whose blocks are half the bytes, 5 to 20 % on batches of a few requests.
+constexpr int kRing = 2;
+
+// What depends on the head dimension and the pool format.
 template <int kD, bool kFp8> struct Dim;
 template <> struct Dim<64, false> {
-  static constexpr int kKSteps = 2, kKLoads = 2, kVLoads = 4, kTiles = 4, kRing = 8, kElemBytes = 2;
+  static constexpr int kKSteps = 2, kKLoads = 2, kVLoads = 4, kTiles = 4, kElemBytes = 2;
   typedef uint32_t VReg __attribute__((ext_vector_type(2)));
 };
 template <> struct Dim<128, false> {
-  static constexpr int kKSteps = 4, kKLoads = 4, kVLoads = 4, kTiles = 8, kRing = 4, kElemBytes = 2;
+  static constexpr int kKSteps = 4, kKLoads = 4, kVLoads = 4, kTiles = 8, kElemBytes = 2;
   typedef uint32_t VReg __attribute__((ext_vector_type(4)));
 };
 template <> struct Dim<256, false> {
-  static constexpr int kKSteps = 8, kKLoads = 8, kVLoads = 8, kTiles = 16, kRing = 4, kElemBytes = 2;
+  static constexpr int kKSteps = 8, kKLoads = 8, kVLoads = 8, kTiles = 16, kElemBytes = 2;
   typedef uint32_t VReg __attribute__((ext_vector_type(4)));
 };
-// K and V stored as one-byte e4m3 values: a block is half the bytes, so the ring is twice as
-// deep; the values are widened to bf16 (exactly) in registers and then take the same path as a
-// bf16 pool.  A K load is 16 bytes = 16 dims of one token and feeds two MFMA steps; a V load is
+// K and V stored as one-byte e4m3 values: the values are widened to bf16 (exactly) in
+// registers and then take the same path as a bf16 pool.  A K load is 16 bytes = 16 dims of one token and feeds two MFMA steps; a V load is
 // the lane's dims of one token (4 bytes at D = 64, 8 bytes otherwise).
 template <> struct Dim<64, true> {
-  static constexpr int kKSteps = 2, kKLoads = 1, kVLoads = 4, kTiles = 4, kRing = 8, kElemBytes = 1;
+  static constexpr int kKSteps = 2, kKLoads = 1, kVLoads = 4, kTiles = 4, kElemBytes = 1;
   typedef uint32_t VReg;
 };
 template <> struct Dim<128, true> {
-  static constexpr int kKSteps = 4, kKLoads = 2, kVLoads = 4, kTiles = 8, kRing = 8, kElemBytes = 1;
+  static constexpr int kKSteps = 4, kKLoads = 2, kVLoads = 4, kTiles = 8, kElemBytes = 1;
   typedef uint32_t VReg __attribute__((ext_vector_type(2)));
 };
 template <> struct Dim<256, true> {
-  static constexpr int kKSteps = 8, kKLoads = 4, kVLoads = 8, kTiles = 16, kRing = 8, kElemBytes = 1;
+  static constexpr int kKSteps = 8, kKLoads = 4, kVLoads = 8, kTiles = 16, kElemBytes = 1;
   typedef uint32_t VReg __attribute__((ext_vector_type(2)));
 };
 // First dim of output tiles 4t..4t+3 (they are consecutive dims) in the lane of column n.
@@ -154,7 +159,7 @@ __global__ __launch_bounds__(kStreamWavesPerGroup * 64) void attn_stream_kernel(
   typedef typename DD::VReg VReg;                 // one V load as it arrives
   typedef typename Dim<kD, false>::VReg VOp;      // the same rows as bf16
   constexpr int kKSteps = DD::kKSteps, kKLoads = DD::kKLoads, kVLoads = DD::kVLoads,
-                kTiles = DD::kTiles, kRing = DD::kRing, kElemBytes = DD::kElemBytes;
+                kTiles = DD::kTiles, kElemBytes = DD::kElemBytes;
   static_assert(kWindow % kRing == 0, "the window must be a whole number of ring turns");
   extern __shared__ int smem[];
   int* cumB = smem;                  // [S+1] blocks before request s
