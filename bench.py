@@ -58,6 +58,10 @@ def parse():
     ap.add_argument("--head-dim", type=int, default=128, choices=[64, 128, 256],
                     help="cfg2 only: the same batch at another head dimension (a workload of its own, "
                          "named ..._d64 / ..._d256)")
+    ap.add_argument("--batch", type=int, default=64,
+                    help="cfg2 only: number of requests (another workload, named for its sizes)")
+    ap.add_argument("--context-range", type=int, nargs=2, default=[1024, 8192], metavar=("LO", "HI"),
+                    help="cfg2 only: context lengths are drawn from U{LO..HI}")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-cfg3", action="store_true", help="default run: skip the long-context sub-record")
     ap.add_argument("--no-migration", action="store_true",
@@ -569,10 +573,16 @@ def main():
         return full_depth(args, dev)
     if args.workload == "cfg5":
         return migration_next_to_decode(args, dev)
-    if args.head_dim != 128 and args.workload != "cfg2":
-        print("bench.py: --head-dim applies to --workload cfg2 only", file=sys.stderr)
+    lo, hi = args.context_range
+    resized = args.head_dim != 128 or args.batch != 64 or [lo, hi] != [1024, 8192]
+    if resized and args.workload != "cfg2":
+        print("bench.py: --head-dim, --batch and --context-range apply to --workload cfg2 only", file=sys.stderr)
         sys.exit(2)
-    w = {"cfg1": wl.cfg1_tiny, "cfg2": lambda: wl.cfg2_qwen32b(head_dim=args.head_dim),
+    if not (1 <= args.batch <= 2048 and 1 <= lo <= hi):
+        print("bench.py: --batch must be 1..2048 and --context-range 1 <= LO <= HI", file=sys.stderr)
+        sys.exit(2)
+    w = {"cfg1": wl.cfg1_tiny,
+         "cfg2": lambda: wl.cfg2_qwen32b(batch=args.batch, lo=lo, hi=hi, head_dim=args.head_dim),
          "cfg3": wl.cfg3_long_cot}[args.workload]()
     if args.partition is not None:
         w.partition_size = args.partition
@@ -593,7 +603,7 @@ def main():
     ok = r.get("parity", {}).get("within_bar", True)
 
     if args.workload == "cfg2" and not args.no_cfg3 and args.partition is None and args.kv_dtype == "bf16" \
-            and args.head_dim == 128:
+            and not resized:
         # The long-context batch as specified (512-token partitions), in the same line.  It is
         # measured by a child process running this script with --workload cfg3, i.e. exactly as a
         # stand-alone run measures it: in a fresh address space (pools allocated after another

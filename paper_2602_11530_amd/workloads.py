@@ -193,7 +193,7 @@ def cfg2_qwen32b(seed: int = BASE_SEED + 2, batch: int = 64,
     lens = rng.integers(lo, hi + 1, size=batch).astype(np.int32)
     nb = int(((lens.astype(np.int64) + BLOCK_SIZE - 1) // BLOCK_SIZE).sum())
     tables = make_tables(lens, nb, rng, maxb=(hi + BLOCK_SIZE - 1) // BLOCK_SIZE)
-    name = "cfg2_qwen32b_b64_u1024_8192" + ("" if head_dim == HEAD_DIM else f"_d{head_dim}")
+    name = f"cfg2_qwen32b_b{batch}_u{lo}_{hi}" + ("" if head_dim == HEAD_DIM else f"_d{head_dim}")
     return Workload(name, 40, 8, lens, tables, nb, head_dim=head_dim, seed=seed)
 
 
