@@ -342,3 +342,23 @@ def test_non_finite_values_in_valid_rows_stay_local(device):
     ref = oracle.paged_decode_attn(q, k2, v2, w.block_tables, w.context_lens, w.scale)
     assert np.array_equal(np.isnan(ref), expect_nan)
     assert np.isposinf(ref[inf_spot]).all()
+
+
+@pytest.mark.parametrize("scale", [0.7, 8.0, -3.0])
+def test_peaked_softmax(device, scale):
+    """Scores hundreds of units apart (a softmax that is all but one-hot, and one turned upside down
+    by a negative scale): the running maximum moves by far more than its lazy bound, old
+    accumulators are rescaled by factors that underflow to zero, and the result still follows the
+    checker."""
+    w = wl.custom([300, 1000, 77, 2100, 1, 16], 40, 8, seed=85, partition_size=256)
+    q, k, v = wl.make_host_tensors(w)
+    got = to_bits(run_attn_dev(w, to_dev(q), to_dev(k), to_dev(v), to_dev(w.block_tables),
+                               to_dev(w.context_lens), scale=scale))
+    torch.cuda.synchronize()
+    ref = oracle.paged_decode_attn(q, k, v, w.block_tables, w.context_lens, np.float32(scale))
+    c = oracle.compare(got, ref)
+    print(f"scale {scale}: {c}", flush=True)
+    assert np.isfinite(wl.bf16_bits_to_f64(got)).all()
+    assert c["rel_l2"] <= REL_L2 and c["worst_seq_rel_l2"] <= 2 * REL_L2, c
+    from gpu_util import abs_error_within_bar
+    assert abs_error_within_bar(got, ref), c       # near one-hot rows reproduce 4-sigma V elements
