@@ -77,12 +77,20 @@ def test_max_context_len_hint_only_shrinks_launch(device):
 
 
 def test_length_one_is_v_bit_exact(device):
+    """A one-token context returns its V row bit for bit — subnormals, the smallest normals and the
+    largest finite values included (request 3 holds them); the one exception is a negative zero,
+    which comes out as +0 (the accumulator starts at +0)."""
     w = wl.custom([1, 1, 1, 1], 40, 8, seed=3, num_pool_blocks=64)
     q, k, v = wl.make_host_tensors(w, poison_unused=True)
+    corners = np.array([0x0001, 0x0040, 0x007F, 0x0080, 0x0081, 0x8001, 0x807F, 0x8080, 0x0000, 0x8000,
+                        0x7F7F, 0xFF7F, 0x0100, 0x3F80, 0x0002, 0x0010] * 8, np.uint16)
+    v[w.block_tables[3, 0], :, 0, :] = corners
     got = run_attn(w, q, k, v).reshape(w.q_shape())
     for s in range(4):
         for h in range(40):
-            assert np.array_equal(got[s, h], v[w.block_tables[s, 0], h // 5, 0])
+            want = v[w.block_tables[s, 0], h // 5, 0].copy()
+            want[want == 0x8000] = 0
+            assert np.array_equal(got[s, h], want)
 
 
 def test_v_ones_gives_exact_ones(device):
