@@ -4,8 +4,10 @@
  * C ABI.  Every pointer marked "device" is HIP device memory owned by the
  * caller; every pointer marked "host" is ordinary host memory read only during
  * the call.  The library allocates nothing, frees nothing and keeps no state
- * between calls, so calls on different streams may overlap as long as their
- * outputs (and workspaces) do not.  Every call validates its host-visible
+ * between calls (apart from the calling thread's fault-counter setting, see
+ * pkv_set_id_fault_counter, and the address of the static workspace, see
+ * paged_decode_attn_static), so calls on different streams may overlap as long
+ * as their outputs (and workspaces) do not.  Every call validates its host-visible
  * arguments first, then enqueues its kernels on `stream` and returns without
  * synchronising.
  *
