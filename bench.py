@@ -348,6 +348,28 @@ def single_layer(args, w, dev, steps, warmup, cpu_baseline):
         "cpu_baseline": None,
     }
 
+    if not fp8 and w.head_dim == 128:
+        # What this box allows for the stream pass's own access pattern (same launch shape and
+        # load instructions over hashed slabs of these pools, no arithmetic): pkv_probe_stream_read.
+        units = int(((w.context_lens.astype(np.int64) + 15) // 16).sum()) * w.num_kv_heads
+        slabs = w.num_pool_blocks * w.num_kv_heads * (w.block_size // 16)
+        for _ in range(5):
+            pkv.pkv_probe_stream_read(k_pool, v_pool, slabs, units, None, stream)
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record(stream)
+        for _ in range(50):
+            pkv.pkv_probe_stream_read(k_pool, v_pool, slabs, units, None, stream)
+        e1.record(stream)
+        torch.cuda.synchronize()
+        probe_ms = e0.elapsed_time(e1) / 50
+        probe_gbps = units * 8192 / (probe_ms * 1e-3) / 1e9
+        res["box_stream_read"] = {
+            "GBps": round(probe_gbps, 1), "ms": round(probe_ms, 4), "bytes": units * 8192,
+            "what": "pkv_probe_stream_read over this batch's block count: the stream pass's launch shape "
+                    "and loads on hashed 4 KiB slabs of the same pools, no arithmetic, timed in this run",
+            "attn_pct_of_it": round(100 * attn_gbps / probe_gbps, 1),
+        }
+
     if cpu_baseline:
         import oracle
         qh = q.view(torch.int16).cpu().numpy().view(np.uint16)
@@ -625,7 +647,8 @@ def main():
                        "total_context_tokens": r3["config"]["total_context_tokens"],
                        "steps": r3["steps"], "attn": r3["attn"], "migration": r3["migration"],
                        "step": r3["step"], "roofline": r3["roofline"],
-                       "cpu_baseline": r3["cpu_baseline"], "parity": r3.get("parity")}
+                       "cpu_baseline": r3["cpu_baseline"], "parity": r3.get("parity"),
+                       "box_stream_read": r3.get("box_stream_read")}
         ok = ok and child.returncode == 0 and (r3.get("parity") or {}).get("within_bar", True)
     print(json.dumps(res), flush=True)
     if not ok:

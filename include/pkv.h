@@ -335,6 +335,25 @@ int kv_append_fp8(const void* k_new, const void* v_new, void* k_pool, void* v_po
  */
 int pkv_set_id_fault_counter(int32_t* device_counter);
 
+/*
+ * Measurement aid (no part of the paper's method): streams total_blocks pairs of
+ * 4 KiB slabs -- the K and the V rows of 16 tokens of one KV head at D = 128 in
+ * bf16 -- out of two buffers with exactly the launch shape and load instructions
+ * of paged_decode_attn's stream pass, at slab numbers drawn by a hash, and does
+ * nothing with the data.  Timed by the caller (events on `stream`), it gives the
+ * rate the machine allows for that access pattern: 8192 * total_blocks bytes per
+ * call.  bench.py reports it next to the attention rate.
+ *
+ *   k_buf, v_buf  device, 16-byte aligned, at least num_slabs * 4096 bytes each
+ *                 (a layer's K and V pool will do: NB * Hkv * B/16 slabs)
+ *   num_slabs     >= 1; the largest power of two not above it is used
+ *   total_blocks  0 .. 2^31-1; 0 is a no-op
+ *   sink          device, 4 bytes, or NULL; never written in practice (it keeps the
+ *                 compiler from dropping the loads)
+ */
+int pkv_probe_stream_read(const void* k_buf, const void* v_buf, int64_t num_slabs,
+                          int64_t total_blocks, void* sink, void* stream);
+
 /* Static text for a status code. */
 const char* pkv_status_string(int status);
 

@@ -27,7 +27,7 @@ EXPORTS = (
     "paged_decode_attn_layers", "paged_decode_attn_static", "paged_decode_attn_fp8kv",
     "kv_blocks_gather", "kv_blocks_scatter", "kv_blocks_move", "kv_blocks_offload", "kv_blocks_reload",
     "kv_append", "kv_append_fp8", "pkv_set_id_fault_counter", "pkv_status_string",
-    "pkv_last_launch_error", "pkv_version",
+    "pkv_last_launch_error", "pkv_version", "pkv_probe_stream_read",
 )
 
 
@@ -99,6 +99,8 @@ def lib() -> ctypes.CDLL:
         L.kv_blocks_offload.restype = ctypes.c_int
         L.kv_blocks_reload.argtypes = [vp, vp, vp, i32p, i64, i64, i64, vp]
         L.kv_blocks_reload.restype = ctypes.c_int
+        L.pkv_probe_stream_read.argtypes = [vp, vp, i64, i64, vp, vp]
+        L.pkv_probe_stream_read.restype = ctypes.c_int
         L.pkv_set_id_fault_counter.argtypes = [vp]
         L.pkv_set_id_fault_counter.restype = ctypes.c_int
         L.kv_append_fp8.argtypes = [vp, vp, vp, vp, i32p, i32p, ctypes.c_float, ctypes.c_float, shp, vp]
@@ -134,6 +136,12 @@ def pkv_set_id_fault_counter(counter) -> None:
     """``counter``: a one-element int32 device tensor that later calls of this thread add the
     number of refused block ids to, or None to switch the report off."""
     _check(lib().pkv_set_id_fault_counter(_ptr(counter)))
+
+
+def pkv_probe_stream_read(k_buf, v_buf, num_slabs: int, total_blocks: int, sink=None, stream=None) -> None:
+    """Measurement aid: the stream pass's loads over ``total_blocks`` hashed slab pairs, no arithmetic."""
+    _check(lib().pkv_probe_stream_read(_ptr(k_buf), _ptr(v_buf), num_slabs, total_blocks, _ptr(sink),
+                                       _stream(stream)))
 
 
 def pkv_version() -> int:

@@ -10,7 +10,8 @@ import sys
 PKG = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(PKG, "csrc")
 LIB = os.path.join(PKG, "libpkv.so")
-SOURCES = ["pkv_api.hip", "attn_stream.hip", "attn_reduce.hip", "kv_copy.hip", "kv_append.hip"]
+SOURCES = ["pkv_api.hip", "attn_stream.hip", "attn_reduce.hip", "kv_copy.hip", "kv_append.hip",
+           "stream_probe.hip"]
 
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 FLAGS = [

@@ -122,7 +122,7 @@ int static_scratch(void** out) {
 
 extern "C" {
 
-int pkv_version(void) { return 1002; }
+int pkv_version(void) { return 1003; }
 
 const char* pkv_status_string(int status) {
   switch (status) {
@@ -143,6 +143,20 @@ int pkv_set_id_fault_counter(int32_t* device_counter) {
   if (reinterpret_cast<uintptr_t>(device_counter) & 3u) return PKV_ERR_ALIGN;
   g_id_faults = device_counter;
   return PKV_OK;
+}
+
+int pkv_probe_stream_read(const void* k_buf, const void* v_buf, int64_t num_slabs,
+                          int64_t total_blocks, void* sink, void* stream) {
+  if (num_slabs < 1 || total_blocks < 0 || total_blocks > INT32_MAX) return PKV_ERR_SHAPE;
+  if (total_blocks == 0) return PKV_OK;
+  if (!k_buf || !v_buf) return PKV_ERR_NULL;
+  if (misaligned16(k_buf) || misaligned16(v_buf) || (reinterpret_cast<uintptr_t>(sink) & 3u))
+    return PKV_ERR_ALIGN;
+  // the largest power of two of slabs that fits (slab numbers are 32-bit)
+  uint32_t pow2 = 1;
+  while ((int64_t)pow2 * 2 <= num_slabs && pow2 < (1u << 30)) pow2 *= 2;
+  return launch_status(pkv::launch_stream_read_probe(k_buf, v_buf, pow2 - 1, total_blocks, sink,
+                                                     static_cast<hipStream_t>(stream)));
 }
 
 int pkv_attn_partition_size(const pkv_attn_shape* shape) {

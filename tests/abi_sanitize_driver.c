@@ -107,6 +107,14 @@ int main(void) {
   EXPECT(kv_append_fp8(p16, p16, p16, p16, i4, i4, -1.f, 1.f, &ok, NULL), PKV_ERR_SHAPE);
   EXPECT(kv_append_fp8(p16, p16, p16, NULL, i4, i4, 1.f, 1.f, &ok, NULL), PKV_ERR_NULL);
 
+  /* the measurement aid */
+  EXPECT(pkv_probe_stream_read(p16, p16, 0, 10, NULL, NULL), PKV_ERR_SHAPE);
+  EXPECT(pkv_probe_stream_read(p16, p16, INT64_MAX, (int64_t)INT32_MAX + 1, NULL, NULL), PKV_ERR_SHAPE);
+  EXPECT(pkv_probe_stream_read(p16, NULL, 64, 10, NULL, NULL), PKV_ERR_NULL);
+  EXPECT(pkv_probe_stream_read(p8, p16, 64, 10, NULL, NULL), PKV_ERR_ALIGN);
+  EXPECT(pkv_probe_stream_read(p16, p16, 64, 10, i2, NULL), PKV_ERR_ALIGN);
+  EXPECT(pkv_probe_stream_read(NULL, NULL, INT64_MAX, 0, NULL, NULL), PKV_OK);
+
   EXPECT(pkv_set_id_fault_counter(i2), PKV_ERR_ALIGN);
   EXPECT(pkv_set_id_fault_counter(NULL), PKV_OK);
   for (int s = 1; s >= -8; --s)

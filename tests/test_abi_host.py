@@ -240,6 +240,16 @@ def test_fp8kv_argument_errors_before_launch():
     assert g(kn=None, vn=None, k=None, v=None, t=None, l=None, shape=sh0) == pkv.PKV_OK
 
 
+def test_stream_probe_argument_errors():
+    L = pkv.lib()
+    f = lambda k=16, v=16, slabs=1024, blocks=100, sink=None: L.pkv_probe_stream_read(k, v, slabs, blocks, sink, None)
+    assert f(slabs=0) == pkv.PKV_ERR_SHAPE and f(blocks=-1) == pkv.PKV_ERR_SHAPE
+    assert f(blocks=2 ** 31) == pkv.PKV_ERR_SHAPE
+    assert f(k=None) == pkv.PKV_ERR_NULL and f(v=None) == pkv.PKV_ERR_NULL
+    assert f(k=24) == pkv.PKV_ERR_ALIGN and f(v=8) == pkv.PKV_ERR_ALIGN and f(sink=6) == pkv.PKV_ERR_ALIGN
+    assert f(k=None, v=None, blocks=0) == pkv.PKV_OK
+
+
 def test_static_call_and_fault_counter_argument_errors():
     L = pkv.lib()
     sh = pkv.make_shape(4, 8, 2, 19, 128)

@@ -370,3 +370,20 @@ def test_peaked_softmax(device, scale):
     assert c["rel_l2"] <= REL_L2 and c["worst_seq_rel_l2"] <= 2 * REL_L2, c
     from gpu_util import abs_error_within_bar
     assert abs_error_within_bar(got, ref), c       # near one-hot rows reproduce 4-sigma V elements
+
+
+def test_stream_read_probe_runs_and_touches_nothing(device):
+    """The measurement aid reads hashed slabs of two buffers and writes nothing: the buffers and a
+    sentinel-filled sink are unchanged, whatever the block count (none, fewer than wavefronts, many)."""
+    from paper_2602_11530_amd import binding as pkv
+    g = torch.Generator(device=device)
+    g.manual_seed(5)
+    a = torch.randint(-2 ** 15, 2 ** 15, (3000 * 2048,), generator=g, device=device, dtype=torch.int16)
+    b = torch.randint(-2 ** 15, 2 ** 15, (3000 * 2048,), generator=g, device=device, dtype=torch.int16)
+    a0, b0 = a.clone(), b.clone()
+    sink = torch.full((4,), 0x5A5A5A5A, dtype=torch.int32, device=device)
+    for blocks in (0, 1, 77, 2048, 100_000):
+        pkv.pkv_probe_stream_read(a, b, 3000, blocks, sink)      # 3000 slabs: 2048 of them are used
+    torch.cuda.synchronize()
+    assert torch.equal(a, a0) and torch.equal(b, b0)
+    assert (sink == 0x5A5A5A5A).all()
