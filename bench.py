@@ -11,7 +11,12 @@ Inputs are resident in HBM before the timed region.  Prints ONE JSON line.
 
 The default run times the Qwen-32B-shaped batch the metric is quoted on and,
 in the same line under "cfg3", the long-context batch at its specified
-512-token partitions.  Other modes: --workload cfg3 | cfg4 | cfg5 | cfg1.
+512-token partitions.  Other modes: --workload cfg3 | cfg4 | cfg5 | cfg1;
+--kv-dtype fp8 (8-bit pools), --head-dim 64|256, --batch N and
+--context-range LO HI (config 2's shape at other sizes), each a workload of its
+own, named as such.  Next to the attention rate the line carries what this box
+delivers for the same access pattern with no arithmetic (box_stream_read) and
+for a plain device-to-device copy (box_copy_bandwidth).
 `--record-traffic` (no GPU) turns two rocprofv3 counter runs of this script
 into profiles/hbm_traffic.json, which later runs quote as roofline.traffic.
 """
