@@ -339,14 +339,15 @@ int pkv_set_id_fault_counter(int32_t* device_counter);
  * Measurement aid (no part of the paper's method): streams total_blocks pairs of
  * 4 KiB slabs -- the K and the V rows of 16 tokens of one KV head at D = 128 in
  * bf16 -- out of two buffers with exactly the launch shape and load instructions
- * of paged_decode_attn's stream pass, at slab numbers drawn by a hash, and does
- * nothing with the data.  Timed by the caller (events on `stream`), it gives the
+ * of paged_decode_attn's stream pass, at slab numbers drawn by a hash that visits
+ * every slab once before it repeats one (so total_blocks <= num_slabs reads
+ * nothing twice and no cache can help), and does nothing with the data.  Timed by the caller (events on `stream`), it gives the
  * rate the machine allows for that access pattern: 8192 * total_blocks bytes per
  * call.  bench.py reports it next to the attention rate.
  *
  *   k_buf, v_buf  device, 16-byte aligned, at least num_slabs * 4096 bytes each
  *                 (a layer's K and V pool will do: NB * Hkv * B/16 slabs)
- *   num_slabs     >= 1; the largest power of two not above it is used
+ *   num_slabs     >= 1 (at most 2^30 are used)
  *   total_blocks  0 .. 2^31-1; 0 is a no-op
  *   sink          device, 4 bytes, or NULL; never written in practice (it keeps the
  *                 compiler from dropping the loads)

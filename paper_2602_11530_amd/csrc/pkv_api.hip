@@ -152,10 +152,9 @@ int pkv_probe_stream_read(const void* k_buf, const void* v_buf, int64_t num_slab
   if (!k_buf || !v_buf) return PKV_ERR_NULL;
   if (misaligned16(k_buf) || misaligned16(v_buf) || (reinterpret_cast<uintptr_t>(sink) & 3u))
     return PKV_ERR_ALIGN;
-  // the largest power of two of slabs that fits (slab numbers are 32-bit)
-  uint32_t pow2 = 1;
-  while ((int64_t)pow2 * 2 <= num_slabs && pow2 < (1u << 30)) pow2 *= 2;
-  return launch_status(pkv::launch_stream_read_probe(k_buf, v_buf, pow2 - 1, total_blocks, sink,
+  // slab numbers are 32-bit on the device; a larger buffer is used up to 2^30 slabs (4 TiB)
+  const uint32_t slabs = num_slabs > ((int64_t)1 << 30) ? (1u << 30) : (uint32_t)num_slabs;
+  return launch_status(pkv::launch_stream_read_probe(k_buf, v_buf, slabs, total_blocks, sink,
                                                      static_cast<hipStream_t>(stream)));
 }
 

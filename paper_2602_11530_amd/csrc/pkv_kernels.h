@@ -109,7 +109,7 @@ hipError_t launch_kv_append_fp8(const uint16_t* k_new, const uint16_t* v_new, vo
                                 int32_t* id_faults, hipStream_t stream);
 
 // Measurement aid: the stream pass's load pattern with no arithmetic (see stream_probe.hip).
-hipError_t launch_stream_read_probe(const void* k_buf, const void* v_buf, uint32_t slab_mask,
+hipError_t launch_stream_read_probe(const void* k_buf, const void* v_buf, uint32_t num_slabs,
                                     int64_t total_blocks, void* sink, hipStream_t stream);
 
 }  // namespace pkv

@@ -4,8 +4,9 @@
 // two 4 KiB reads per 16-token block of one KV head at D = 128 in bf16 -- a "K"
 // slab in matrix-operand order (a 64-byte run per token row per load) and a "V"
 // slab in natural order -- the same nontemporal loads with one block in flight,
-// but the slabs are picked by a multiplicative hash instead of a block table and
-// the data is only XOR-ed.  What the attention kernel loses against this figure
+// but the slabs are picked by a hash instead of a block table -- a bijection, so
+// that no slab is read twice while total_blocks <= num_slabs and nothing can be
+// served by a cache -- and the data is only XOR-ed.  What the attention kernel loses against this figure
 // is its own doing (descriptor chain, softmax and matrix products, records);
 // what this figure loses against the nominal HBM rate is the machine's.
 #include "pkv_kernels.h"
@@ -16,8 +17,8 @@ namespace {
 constexpr int kSlabUnits = 256;   // 16-byte units in a 4 KiB slab
 
 __global__ __launch_bounds__(kStreamWavesPerGroup * 64) void stream_read_probe_kernel(
-    const u32x4* __restrict__ k_buf, const u32x4* __restrict__ v_buf, uint32_t slab_mask,
-    int64_t total_blocks, int waves, uint32_t* __restrict__ sink) {
+    const u32x4* __restrict__ k_buf, const u32x4* __restrict__ v_buf, uint32_t num_slabs,
+    uint32_t pow2_mask, int64_t total_blocks, int waves, uint32_t* __restrict__ sink) {
   const int w = blockIdx.x * kStreamWavesPerGroup + (threadIdx.x >> 6);
   const int lane = threadIdx.x & 63;
   const int n = lane & 15, c = lane >> 4;
@@ -28,7 +29,13 @@ __global__ __launch_bounds__(kStreamWavesPerGroup * 64) void stream_read_probe_k
   u32x4 kb[2][4], vb[2][4];
   // unconditional loads, as in the stream pass: an index past the share reads slab 0
   auto issue = [&](u32x4 (&k)[4], u32x4 (&v)[4], int j) {
-    const uint32_t slab = j < nshare ? ((uint32_t)(p0 + j) * 2654435761u) & slab_mask : 0u;
+    // x -> (x * odd + c) mod 2^k permutes [0, 2^k); re-applying it until the value falls below
+    // num_slabs (fewer than two rounds on average) permutes [0, num_slabs)
+    uint32_t slab = 0;
+    if (j < nshare) {
+      slab = (uint32_t)((p0 + j) % num_slabs);
+      do slab = (slab * 2654435761u + 0x9e3779b9u) & pow2_mask; while (slab >= num_slabs);
+    }
     const u32x4* kp = k_buf + (int64_t)slab * kSlabUnits + koff;
     const u32x4* vp = v_buf + (int64_t)slab * kSlabUnits + lane;
 #pragma unroll
@@ -53,11 +60,14 @@ __global__ __launch_bounds__(kStreamWavesPerGroup * 64) void stream_read_probe_k
 
 }  // namespace
 
-hipError_t launch_stream_read_probe(const void* k_buf, const void* v_buf, uint32_t slab_mask,
+hipError_t launch_stream_read_probe(const void* k_buf, const void* v_buf, uint32_t num_slabs,
                                     int64_t total_blocks, void* sink, hipStream_t stream) {
+  uint32_t pow2 = 1;   // the smallest power of two >= num_slabs (num_slabs <= 2^30)
+  while (pow2 < num_slabs) pow2 *= 2;
   const dim3 grid(kStreamGroups), block(kStreamWavesPerGroup * 64);
   hipLaunchKernelGGL(stream_read_probe_kernel, grid, block, 0, stream, (const u32x4*)k_buf,
-                     (const u32x4*)v_buf, slab_mask, total_blocks, kStreamWaves, (uint32_t*)sink);
+                     (const u32x4*)v_buf, num_slabs, pow2 - 1, total_blocks, kStreamWaves,
+                     (uint32_t*)sink);
   return hipGetLastError();
 }
 

@@ -383,7 +383,7 @@ def test_stream_read_probe_runs_and_touches_nothing(device):
     a0, b0 = a.clone(), b.clone()
     sink = torch.full((4,), 0x5A5A5A5A, dtype=torch.int32, device=device)
     for blocks in (0, 1, 77, 2048, 100_000):
-        pkv.pkv_probe_stream_read(a, b, 3000, blocks, sink)      # 3000 slabs: 2048 of them are used
+        pkv.pkv_probe_stream_read(a, b, 3000, blocks, sink)      # 3000 slabs
     torch.cuda.synchronize()
     assert torch.equal(a, a0) and torch.equal(b, b0)
     assert (sink == 0x5A5A5A5A).all()
