@@ -24,7 +24,7 @@ template <> struct Chunk<1> { typedef float T; };
 template <int kPer> __device__ __forceinline__ float chunk_get(const typename Chunk<kPer>::T& v, int i) { return v[i]; }
 template <> __device__ __forceinline__ float chunk_get<1>(const float& v, int) { return v; }
 
-// fp32 -> bf16, round to nearest even (inputs here are finite)
+// fp32 -> bf16, round to nearest even (a NaN stays a NaN)
 __device__ __forceinline__ uint16_t bf16_bits(float x) {
   typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
   typedef float f32x2 __attribute__((ext_vector_type(2)));
